@@ -1,0 +1,227 @@
+"""CPU oracle for the CoPRIS rollout-decode hot path.  TEST INFRASTRUCTURE ONLY.
+
+A plain, slow, fp64 numpy statement of what one decode step and the cross-stage
+importance-sampling ratio compute.  It exists to check the HIP kernels; it is
+not a fallback.  Only tests, the smoke check and the benchmark's `cpu_baseline`
+leg may import it.  It shares no code with the HIP path and imports nothing
+from the product package.
+
+Every function is pinned by CPU-only tests against something other than itself
+(brute-force loops on tiny inputs, library softmax / logsumexp, closed forms,
+invariants, published Philox known-answer vectors); none is "parity unpinned".
+
+What the paper fixes and what it leaves open:
+
+* The paper runs generation inside a third-party inference engine (Appendix
+  A.2) and gives no formula for attention, the LM head or the sampler.  Those
+  are therefore the textbook definitions: scaled dot-product softmax attention
+  of the one new query against the sequence's cached keys and values,
+  log-softmax of the LM-head logits, and an exact draw from softmax(z / T).
+* Table 4 fixes the sampler: temperature 1.0, top-p 1.0, top-k -1, i.e. the
+  untruncated softmax.  Gumbel-max (argmax_v z_v + G_v with G_v iid standard
+  Gumbel) is an exact sampler of that distribution.
+* Section 4 ("Buffering of Partial Trajectories", Eq. 6) keeps, for each
+  generated token, its log-probability under the policy that generated it.
+* Section 4 ("Cross-stage Importance Sampling Correction", Eq. 8) defines the
+  token ratio r = exp(L_cur - L_buffered); Eq. 3 clips it to [1-eps, 1+eps]
+  (Table 4 lists separate low / high clip ratios, hence two epsilons).
+"""
+from __future__ import annotations
+
+import numpy as np
+
+# --------------------------------------------------------------------------
+# Philox4x32-10 (Salmon, Moraes, Dror, Shaw: "Parallel random numbers: as easy
+# as 1, 2, 3", SC'11).  Counter-based generator: 128-bit counter, 64-bit key,
+# ten rounds.  Written with numpy uint64 lanes so whole vocab rows go at once.
+# --------------------------------------------------------------------------
+_PHILOX_M0 = np.uint64(0xD2511F53)
+_PHILOX_M1 = np.uint64(0xCD9E8D57)
+_PHILOX_W0 = np.uint64(0x9E3779B9)
+_PHILOX_W1 = np.uint64(0xBB67AE85)
+_MASK32 = np.uint64(0xFFFFFFFF)
+_SH32 = np.uint64(32)
+
+
+def philox4x32_10(counter, key):
+    """counter: 4 arrays (or scalars) of 32-bit words c0..c3; key: 2 words k0,k1.
+    Returns 4 uint32 arrays x0..x3 (broadcast shape of the inputs)."""
+    c0, c1, c2, c3 = [np.asarray(c, dtype=np.uint64) & _MASK32 for c in counter]
+    k0, k1 = [np.asarray(k, dtype=np.uint64) & _MASK32 for k in key]
+    c0, c1, c2, c3, k0, k1 = np.broadcast_arrays(c0, c1, c2, c3, k0, k1)
+    for rnd in range(10):
+        if rnd > 0:
+            k0 = (k0 + _PHILOX_W0) & _MASK32
+            k1 = (k1 + _PHILOX_W1) & _MASK32
+        p0 = _PHILOX_M0 * c0          # 32x32 -> 64 bit, no overflow in uint64
+        p1 = _PHILOX_M1 * c2
+        hi0, lo0 = p0 >> _SH32, p0 & _MASK32
+        hi1, lo1 = p1 >> _SH32, p1 & _MASK32
+        c0, c1, c2, c3 = hi1 ^ c1 ^ k0, lo1, hi0 ^ c3 ^ k1, lo0
+    return tuple(c.astype(np.uint32) for c in (c0, c1, c2, c3))
+
+
+def sampling_uniforms(seed: int, seq_id: int, step: int, V: int) -> np.ndarray:
+    """The V uniforms of the stream Philox(seed, seq, step), fp64 in (0, 1).
+
+    Vocabulary entry v takes word (v & 3) of the block whose counter is
+    (v >> 2, step, seq_id low word, seq_id high word) under the key
+    (seed low word, seed high word).  A word x maps to the midpoint of one of
+    2^23 equal cells: u = ((x >> 9) + 0.5) / 2^23, which is exact in fp32 and
+    never 0 or 1.  The stream depends on the trajectory and its token index
+    only, never on the batch slot, so a resumed trajectory continues it.
+    """
+    seed = int(seed) & 0xFFFFFFFFFFFFFFFF
+    sid = int(seq_id) & 0xFFFFFFFFFFFFFFFF
+    nblk = (V + 3) // 4
+    blk = np.arange(nblk, dtype=np.uint64)
+    x = philox4x32_10((blk, int(step) & 0xFFFFFFFF, sid & 0xFFFFFFFF, sid >> 32),
+                      (seed & 0xFFFFFFFF, seed >> 32))
+    words = np.stack(x, axis=1).reshape(-1)[:V]          # v -> word v&3 of block v>>2
+    return ((words >> np.uint32(9)).astype(np.float64) + 0.5) * (2.0 ** -23)
+
+
+def gumbel_noise(seed: int, seq_id: int, step: int, V: int) -> np.ndarray:
+    """Standard Gumbel variates G_v = -ln(-ln u_v) for one (trajectory, token)."""
+    u = sampling_uniforms(seed, seq_id, step, V)
+    return -np.log(-np.log(u))
+
+
+# --------------------------------------------------------------------------
+# O1: paged-KV grouped-query decode attention
+# --------------------------------------------------------------------------
+def decode_attn(q, k_cache, v_cache, block_table, ctx_len, scale, page_size=None):
+    """Softmax attention of each sequence's single new query over its context.
+
+    q           [C, Hq, D]
+    k_cache     [num_pages, Hkv, P, D]   (v_cache alike)
+    block_table [C, max_pages] int       logical page j of seq i -> physical page
+    ctx_len     [C] int                  tokens whose K/V are cached (includes
+                                          the current token); entries of the
+                                          block table past ceil(ctx/P) are ignored
+    Query head h reads KV head h // (Hq // Hkv).
+    Token t of a sequence lives in page block_table[i, t // P], slot t % P.
+    Returns (out [C, Hq, D] fp64, lse [C, Hq] fp64); a sequence of length 0
+    gives out = 0 and lse = -inf.
+    """
+    q = np.asarray(q, dtype=np.float64)
+    C, Hq, D = q.shape
+    _, Hkv, P, Dk = k_cache.shape
+    assert Dk == D and Hq % Hkv == 0
+    if page_size is not None:
+        assert page_size == P
+    g = Hq // Hkv
+    out = np.zeros((C, Hq, D), dtype=np.float64)
+    lse = np.full((C, Hq), -np.inf, dtype=np.float64)
+    for i in range(C):
+        n = int(ctx_len[i])
+        if n == 0:
+            continue
+        npg = (n + P - 1) // P
+        pages = np.asarray(block_table[i, :npg], dtype=np.int64)
+        for kvh in range(Hkv):
+            K = np.asarray(k_cache[pages, kvh], dtype=np.float64).reshape(npg * P, D)[:n]
+            Vv = np.asarray(v_cache[pages, kvh], dtype=np.float64).reshape(npg * P, D)[:n]
+            for h in range(kvh * g, (kvh + 1) * g):
+                s = scale * (K @ q[i, h])
+                m = s.max()
+                p = np.exp(s - m)
+                denom = p.sum()
+                out[i, h] = (p @ Vv) / denom
+                lse[i, h] = m + np.log(denom)
+    return out, lse
+
+
+# --------------------------------------------------------------------------
+# O2: LM head + log-softmax + Gumbel-max sample + chosen-token log-prob
+# --------------------------------------------------------------------------
+def lmhead_logprob(hidden, weight, seq_id, step, seed, temperature, return_full=False):
+    """For every row c: z = (hidden[c] . weight[v]) / T over the vocabulary,
+    lse = logsumexp(z), token = argmax_v (z_v + G_v) with the Gumbel variates of
+    Philox(seed, seq_id[c], step[c]) (lowest index on an exact tie), and
+    logprob = z[token] - lse: the log-probability, under the generating policy,
+    that the buffer keeps for the token (Section 4, Eq. 6).
+
+    Returns a dict: token int32 [C], logprob [C], lse [C], best [C] and
+    runner_up [C] (the two largest perturbed scores), second_token int32 [C],
+    and with return_full the full log-softmax matrix `logp` [C, V].
+    """
+    h = np.asarray(hidden, dtype=np.float64)
+    w = np.asarray(weight, dtype=np.float64)
+    C = h.shape[0]
+    V = w.shape[0]
+    z = (h @ w.T) / float(temperature)
+    zmax = z.max(axis=1, keepdims=True)
+    lse = (zmax + np.log(np.exp(z - zmax).sum(axis=1, keepdims=True)))[:, 0]
+    token = np.empty(C, dtype=np.int32)
+    second = np.empty(C, dtype=np.int32)
+    best = np.empty(C)
+    runner = np.empty(C)
+    for c in range(C):
+        score = z[c] + gumbel_noise(seed, int(seq_id[c]), int(step[c]), V)
+        t = int(np.argmax(score))            # first index of the maximum
+        token[c] = t
+        best[c] = score[t]
+        if V > 1:
+            score[t] = -np.inf
+            t2 = int(np.argmax(score))
+            second[c] = t2
+            runner[c] = score[t2]
+        else:
+            second[c] = t
+            runner[c] = -np.inf
+    res = {"token": token, "logprob": z[np.arange(C), token] - lse, "lse": lse,
+           "best": best, "runner_up": runner, "second_token": second}
+    if return_full:
+        res["logp"] = z - lse[:, None]
+    return res
+
+
+# --------------------------------------------------------------------------
+# O3: token-level cross-stage importance ratio, clip, masked per-sequence sums
+# --------------------------------------------------------------------------
+def is_ratio(logp_cur, logp_buf, logp_roll, cu_seqlens, split, mask, eps_low, eps_high):
+    """Eq. 8 with the clip of Eq. 3, over a packed batch.
+
+    Sequence b owns tokens cu_seqlens[b] .. cu_seqlens[b+1]-1.  Its first
+    split[b] tokens were generated in earlier stages, so their old-policy
+    log-probs are the buffered ones (logp_buf); the rest were generated in the
+    current rollout stage (logp_roll).  By Eq. 6 the buffer of a trajectory that
+    spans K stages is one flat vector in token order, so K never appears here.
+    For a counted token: r = exp(cur - old), rc = min(max(r, 1-eps_low), 1+eps_high).
+    A masked token (mask == 0) gives 0 in both outputs and is not counted; the
+    side of the split that is not selected is never read.
+
+    Returns ratio [N], ratio_clipped [N] (fp64), seq_sum [B] (sum of rc over
+    counted tokens), seq_cnt [B], seq_nclip [B] (counted tokens with rc != r).
+    """
+    cur = np.asarray(logp_cur, dtype=np.float64)
+    buf = np.asarray(logp_buf, dtype=np.float64)
+    roll = np.asarray(logp_roll, dtype=np.float64)
+    cu = np.asarray(cu_seqlens, dtype=np.int64)
+    B = cu.size - 1
+    N = cur.size
+    ratio = np.zeros(N)
+    clipped = np.zeros(N)
+    seq_sum = np.zeros(B)
+    seq_cnt = np.zeros(B, dtype=np.int64)
+    seq_nclip = np.zeros(B, dtype=np.int64)
+    lo = 1.0 - float(eps_low)
+    hi = 1.0 + float(eps_high)
+    for b in range(B):
+        s, e = int(cu[b]), int(cu[b + 1])
+        if e <= s:
+            continue
+        k = min(max(int(split[b]), 0), e - s)
+        old = np.concatenate([buf[s:s + k], roll[s + k:e]])
+        counted = np.ones(e - s, dtype=bool) if mask is None else (np.asarray(mask[s:e]) != 0)
+        with np.errstate(over="ignore", invalid="ignore"):
+            r = np.exp(cur[s:e] - old)
+        rc = np.minimum(np.maximum(r, lo), hi)
+        ratio[s:e] = np.where(counted, r, 0.0)
+        clipped[s:e] = np.where(counted, rc, 0.0)
+        seq_sum[b] = rc[counted].sum()
+        seq_cnt[b] = int(counted.sum())
+        seq_nclip[b] = int((rc[counted] != r[counted]).sum())
+    return {"ratio": ratio, "ratio_clipped": clipped, "seq_sum": seq_sum,
+            "seq_cnt": seq_cnt, "seq_nclip": seq_nclip}
