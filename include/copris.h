@@ -1,0 +1,182 @@
+/*
+ * copris.h - C ABI of the CoPRIS rollout-decode hot path on MI355X (gfx950).
+ *
+ * One decode step of a fixed concurrency pool of C requests (Section 4,
+ * "Concurrency-Controlled Generation": N' requests stay in flight) with ragged,
+ * long-tailed context lengths (Section 3.2), some of them partial trajectories
+ * resumed from the buffer (Section 4, "Prioritized Resumption"):
+ *
+ *   copris_decode_attn     paged-KV grouped-query decode attention
+ *   copris_lmhead_logprob  LM-head projection fused with log-softmax, Gumbel-max
+ *                          sampling and the chosen token's log-probability: the
+ *                          per-token log-prob under the generating policy that the
+ *                          buffer keeps (Section 4, "Buffering of Partial
+ *                          Trajectories", Eq. 6)
+ *   copris_is_ratio        token-level cross-stage importance ratio (Section 4,
+ *                          "Cross-stage Importance Sampling Correction", Eq. 8)
+ *                          with the clip of Eq. 3 and masked per-sequence sums
+ *
+ * Conventions
+ *   - Plain C.  Every pointer argument is a DEVICE pointer owned by the caller,
+ *     unless stated otherwise.  The library allocates nothing, never
+ *     synchronises and never copies to the host: every call only enqueues
+ *     kernels on `stream` (a hipStream_t passed as void*; NULL = the null
+ *     stream) and returns.
+ *   - Outputs are fully overwritten; inputs are never modified.  No global
+ *     state: calls are re-entrant across streams given disjoint workspaces and
+ *     outputs.
+ *   - Tensors are dense, row-major, last index fastest, and their base
+ *     addresses must be 16-byte aligned.
+ *   - dtype: COPRIS_F32 (0) or COPRIS_BF16 (1).  bf16 tensors accumulate in fp32.
+ *   - Return value: COPRIS_OK (0) or a negative error code.  Arguments are
+ *     checked on the host without touching device memory; a rejected call
+ *     enqueues nothing.  The CONTENTS of device arrays (a block-table entry
+ *     outside [0, num_pages), cu_seqlens that do not increase, ...) cannot be
+ *     checked without a device round trip and are the caller's responsibility.
+ */
+#ifndef COPRIS_H
+#define COPRIS_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define COPRIS_OK            0
+#define COPRIS_EINVAL       -1   /* null pointer, bad shape, misaligned base, bad scalar */
+#define COPRIS_EWORKSPACE   -2   /* workspace smaller than the *_workspace_bytes query   */
+#define COPRIS_EUNSUPPORTED -3   /* dtype / head_dim / page_size / group size not built  */
+#define COPRIS_ELAUNCH      -4   /* the HIP runtime reported an error at launch          */
+
+#define COPRIS_F32  0
+#define COPRIS_BF16 1
+
+/* Text for an error code (static storage, host pointer, never NULL). */
+const char* copris_strerror(int code);
+
+/* Library version, "major.minor.patch" (static storage, host pointer). */
+const char* copris_version(void);
+
+/* After a call on this thread returned COPRIS_ELAUNCH: which kernel failed to launch
+ * and the HIP runtime's error text (thread-local storage, host pointer, "" if none). */
+const char* copris_last_error_detail(void);
+
+/* ------------------------------------------------------------------------
+ * Paged-KV grouped-query decode attention.
+ *
+ * The paper runs generation inside an inference engine (Appendix A.2) and
+ * states no formula; the operation is softmax attention of each request's one
+ * new query over its own cached context:
+ *
+ *   for sequence i, query head h, kv head kvh = h / (Hq/Hkv), tokens t < ctx_len[i]:
+ *     page = block_table[i][t / page_size],  slot = t % page_size
+ *     s_t  = scale * sum_d q[i][h][d] * k_cache[page][kvh][slot][d]
+ *     out[i][h][:] = sum_t softmax(s)_t * v_cache[page][kvh][slot][:]
+ *     lse[i][h]    = log sum_t exp(s_t)
+ *
+ * Work is split along the context (fixed-size token chunks, merged in chunk
+ * order), so a few very long resumed trajectories do not serialise the step;
+ * the result does not depend on the physical page order.
+ *
+ *   q           [C, Hq, D]                      dtype
+ *   k_cache     [num_pages, Hkv, page_size, D]  dtype; RoPE already applied
+ *   v_cache     [num_pages, Hkv, page_size, D]  dtype
+ *   block_table [C, max_pages] int32; entries at or past ceil(ctx_len/page_size)
+ *               are ignored (may hold anything)
+ *   ctx_len     [C] int32, 0 <= ctx_len[i] <= max_pages*page_size; counts every
+ *               token whose K/V is in the cache, the current one included
+ *   out         [C, Hq, D] dtype (bf16: rounded to nearest even)
+ *   lse         [C, Hq] fp32, or NULL
+ *   workspace   device scratch of at least copris_decode_attn_workspace_bytes()
+ *               bytes, 256-byte aligned; contents on entry and exit are arbitrary
+ *   scale       usually 1/sqrt(D)
+ *
+ * Slots of a last page at or past ctx_len, and pages the block table does not
+ * reference, are never allowed to influence the result (they may hold NaN).
+ * ctx_len[i] == 0 gives out = 0, lse = -inf.
+ * Supported: D in {64, 128}; page_size 16; Hq/Hkv <= 16; C*Hkv < 2^20.
+ * ------------------------------------------------------------------------ */
+size_t copris_decode_attn_workspace_bytes(int C, int Hq, int Hkv, int D,
+                                          int page_size, int max_pages);
+
+int copris_decode_attn(const void* q, const void* k_cache, const void* v_cache,
+                       const int32_t* block_table, const int32_t* ctx_len,
+                       void* out, float* lse,
+                       void* workspace, size_t workspace_bytes,
+                       int C, int Hq, int Hkv, int D, int page_size, int max_pages,
+                       int64_t num_pages, float scale, int dtype, void* stream);
+
+/* ------------------------------------------------------------------------
+ * LM head fused with log-softmax, Gumbel-max sampling and log-prob gather.
+ *
+ * Table 4 fixes the rollout sampler (temperature 1.0, top-p 1.0, top-k -1): one
+ * draw from the untruncated softmax.  Section 4 (Eq. 6) keeps the drawn token's
+ * log-probability under the generating policy.  For every row c:
+ *
+ *   z_v     = (sum_k hidden[c][k] * weight[v][k]) / temperature      v = 0..V-1
+ *   lse     = log sum_v exp(z_v)
+ *   u_v     = uniform of Philox4x32-10 (Salmon et al., SC'11):
+ *               key     = (seed & 0xffffffff, seed >> 32)
+ *               counter = (v >> 2, step[c], seq_id[c] & 0xffffffff, seq_id[c] >> 32)
+ *               x       = output word (v & 3);  u_v = ((x >> 9) + 0.5) * 2^-23
+ *   token   = argmax_v (z_v - ln(-ln u_v))      (lowest v on an exact tie)
+ *   logprob = z_token - lse
+ *
+ * The V logits are never written to memory; the weight matrix is streamed once.
+ * The random stream depends on (seed, seq_id, step) only - not on the slot c,
+ * the batch size or the launch shape - so a resumed trajectory continues it.
+ *
+ *   hidden  [C, H] dtype            weight [V, H] dtype (row v = vocabulary entry v)
+ *   seq_id  [C] int64  stable trajectory id (not the slot index)
+ *   step    [C] int32  index of the token being generated within its response
+ *   token   [C] int32 out     logprob [C] fp32 out     lse [C] fp32 out or NULL
+ *   workspace  at least copris_lmhead_logprob_workspace_bytes() bytes, 256-byte aligned
+ *
+ * Requires temperature > 0, H % 8 == 0 for bf16 (H % 4 == 0 for fp32), V < 2^31.
+ * ------------------------------------------------------------------------ */
+size_t copris_lmhead_logprob_workspace_bytes(int C, int H, int V);
+
+int copris_lmhead_logprob(const void* hidden, const void* weight,
+                          const int64_t* seq_id, const int32_t* step,
+                          uint64_t seed, float temperature,
+                          int32_t* token, float* logprob, float* lse,
+                          void* workspace, size_t workspace_bytes,
+                          int C, int H, int V, int dtype, void* stream);
+
+/* ------------------------------------------------------------------------
+ * Token-level cross-stage importance ratio over a packed batch.
+ *
+ * Eq. 8: r = exp(L_cur - L_old); Eq. 3: clip(r, 1-eps_low, 1+eps_high) (Table 4
+ * lists clip ratio low and high separately).  By Eq. 6 the buffered log-probs of
+ * a trajectory that spans several stages are one vector in token order, so a
+ * trajectory is described by one number: split[b], how many of its tokens were
+ * generated in earlier stages.  For sequence b, local index t, j = cu_seqlens[b]+t:
+ *
+ *   old = t < split[b] ? logp_buf[j] : logp_roll[j]     (the other side is not read)
+ *   if mask && !mask[j]:  ratio[j] = ratio_clipped[j] = 0, token not counted
+ *   else r = exp(logp_cur[j] - old); rc = min(max(r, 1-eps_low), 1+eps_high)
+ *        seq_sum[b] += rc; seq_cnt[b] += 1; seq_nclip[b] += (rc != r)
+ *
+ * Nothing is clamped before the exponential: an overflow to +inf is clipped to
+ * 1+eps_high; NaN in a counted input propagates.  Sums are formed in a fixed
+ * order (bitwise reproducible).
+ *
+ *   logp_cur, logp_buf, logp_roll [N] fp32      cu_seqlens [B+1] int32, cu[0]=0, cu[B]=N
+ *   split [B] int32 in 0..len_b                 mask [N] uint8 or NULL (all counted)
+ *   ratio, ratio_clipped [N] fp32 out           seq_sum [B] fp32, seq_cnt, seq_nclip [B] int32 out
+ *
+ * Requires 0 <= eps_low < 1, eps_high >= 0, B >= 0, 0 <= N < 2^31.
+ * ------------------------------------------------------------------------ */
+int copris_is_ratio(const float* logp_cur, const float* logp_buf, const float* logp_roll,
+                    const int32_t* cu_seqlens, const int32_t* split, const uint8_t* mask,
+                    float eps_low, float eps_high,
+                    float* ratio, float* ratio_clipped,
+                    float* seq_sum, int32_t* seq_cnt, int32_t* seq_nclip,
+                    int B, int64_t N, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* COPRIS_H */

@@ -1,0 +1,139 @@
+"""Thin ctypes binding of libcopris.so: argument marshalling only.
+
+Every step of the path runs in the library's HIP kernels.  PyTorch is used for
+device memory and stream handles, nothing else.  There is no CPU fallback: if
+the shared library is missing the import of a symbol fails loudly.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from ctypes import c_char_p, c_float, c_int, c_int64, c_size_t, c_uint64, c_void_p
+from typing import Optional
+
+_PKG_DIR = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG_DIR, "libcopris.so")
+
+COPRIS_OK = 0
+COPRIS_EINVAL = -1
+COPRIS_EWORKSPACE = -2
+COPRIS_EUNSUPPORTED = -3
+COPRIS_ELAUNCH = -4
+COPRIS_F32 = 0
+COPRIS_BF16 = 1
+
+# name -> (restype, argtypes), mirroring include/copris.h
+SIGNATURES = {
+    "copris_strerror": (c_char_p, [c_int]),
+    "copris_version": (c_char_p, []),
+    "copris_last_error_detail": (c_char_p, []),
+    "copris_decode_attn_workspace_bytes": (c_size_t, [c_int] * 6),
+    "copris_decode_attn": (c_int, [c_void_p] * 8 + [c_size_t] + [c_int] * 6 + [c_int64, c_float, c_int, c_void_p]),
+    "copris_lmhead_logprob_workspace_bytes": (c_size_t, [c_int] * 3),
+    "copris_lmhead_logprob": (c_int, [c_void_p] * 4 + [c_uint64, c_float] + [c_void_p] * 4
+                              + [c_size_t] + [c_int] * 4 + [c_void_p]),
+    "copris_is_ratio": (c_int, [c_void_p] * 6 + [c_float, c_float] + [c_void_p] * 5
+                        + [c_int, c_int64, c_void_p]),
+}
+
+_lib = None
+
+
+class CoprisError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = code
+        detail = load_library().copris_last_error_detail().decode() if code == COPRIS_ELAUNCH else ""
+        super().__init__(f"{where}: {strerror(code)} (code {code}) {detail}".rstrip())
+
+
+def load_library(path: Optional[str] = None) -> ctypes.CDLL:
+    """Load libcopris.so (built in-tree by paper_2511_05589_amd.build) and type its symbols."""
+    global _lib
+    if _lib is not None and path is None:
+        return _lib
+    path = path or LIB_PATH
+    if not os.path.exists(path):
+        raise FileNotFoundError(
+            f"{path} not found: build it with `python -m paper_2511_05589_amd.build` "
+            "(there is no fallback path)")
+    # PyTorch ships its own HIP runtime (same soname as the system one).  Import it
+    # first so that the loader binds libcopris to that already-loaded copy: two HIP
+    # runtimes in one process cannot share streams or device memory.
+    import torch  # noqa: F401
+    lib = ctypes.CDLL(path)
+    for name, (res, args) in SIGNATURES.items():
+        fn = getattr(lib, name)          # AttributeError if the symbol is not exported
+        fn.restype = res
+        fn.argtypes = args
+    _lib = lib
+    return lib
+
+
+def strerror(code: int) -> str:
+    return load_library().copris_strerror(int(code)).decode()
+
+
+def version() -> str:
+    return load_library().copris_version().decode()
+
+
+def _ptr(t) -> Optional[int]:
+    return None if t is None else t.data_ptr()
+
+
+def _stream(stream) -> Optional[int]:
+    if stream is None:
+        import torch
+        stream = torch.cuda.current_stream()
+    h = stream.cuda_stream
+    return h if h else None
+
+
+def _check(code: int, where: str) -> None:
+    if code != COPRIS_OK:
+        raise CoprisError(code, where)
+
+
+def decode_attn_workspace_bytes(C, Hq, Hkv, D, page_size, max_pages) -> int:
+    return int(load_library().copris_decode_attn_workspace_bytes(C, Hq, Hkv, D, page_size, max_pages))
+
+
+def decode_attn(q, k_cache, v_cache, block_table, ctx_len, out, lse, workspace, *, scale: float,
+                dtype: int, stream=None) -> None:
+    """copris_decode_attn on device tensors (shapes as in include/copris.h)."""
+    C, Hq, D = q.shape
+    num_pages, Hkv, page_size, _ = k_cache.shape
+    max_pages = block_table.shape[1]
+    code = load_library().copris_decode_attn(
+        _ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(block_table), _ptr(ctx_len), _ptr(out),
+        _ptr(lse), _ptr(workspace), workspace.numel() * workspace.element_size(),
+        C, Hq, Hkv, D, page_size, max_pages, num_pages, float(scale), int(dtype), _stream(stream))
+    _check(code, "copris_decode_attn")
+
+
+def lmhead_logprob_workspace_bytes(C, H, V) -> int:
+    return int(load_library().copris_lmhead_logprob_workspace_bytes(C, H, V))
+
+
+def lmhead_logprob(hidden, weight, seq_id, step, token, logprob, lse, workspace, *, seed: int,
+                   temperature: float, dtype: int, stream=None) -> None:
+    """copris_lmhead_logprob on device tensors."""
+    C, H = hidden.shape
+    V = weight.shape[0]
+    code = load_library().copris_lmhead_logprob(
+        _ptr(hidden), _ptr(weight), _ptr(seq_id), _ptr(step), int(seed) & 0xFFFFFFFFFFFFFFFF,
+        float(temperature), _ptr(token), _ptr(logprob), _ptr(lse), _ptr(workspace),
+        workspace.numel() * workspace.element_size(), C, H, V, int(dtype), _stream(stream))
+    _check(code, "copris_lmhead_logprob")
+
+
+def is_ratio(logp_cur, logp_buf, logp_roll, cu_seqlens, split, mask, ratio, ratio_clipped,
+             seq_sum, seq_cnt, seq_nclip, *, eps_low: float, eps_high: float, stream=None) -> None:
+    """copris_is_ratio on device tensors."""
+    B = cu_seqlens.numel() - 1
+    N = logp_cur.numel()
+    code = load_library().copris_is_ratio(
+        _ptr(logp_cur), _ptr(logp_buf), _ptr(logp_roll), _ptr(cu_seqlens), _ptr(split), _ptr(mask),
+        float(eps_low), float(eps_high), _ptr(ratio), _ptr(ratio_clipped), _ptr(seq_sum),
+        _ptr(seq_cnt), _ptr(seq_nclip), B, N, _stream(stream))
+    _check(code, "copris_is_ratio")

@@ -1,0 +1,59 @@
+// Host-side declarations shared by the C ABI and the kernel launchers.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace copris {
+
+// Checks hipGetLastError() after a launch; on failure records "<kernel>: <hip error>" for
+// copris_last_error_detail() and returns false.
+bool launch_ok(const char* kernel_name);
+constexpr int kErrLaunch = -4;   // COPRIS_ELAUNCH
+#define COPRIS_CHECK_LAUNCH(name) \
+  do {                            \
+    if (!::copris::launch_ok(name)) return ::copris::kErrLaunch; \
+  } while (0)
+
+// ---- decode attention -------------------------------------------------------
+constexpr int kAttnChunkTokens = 512;   // split-K granularity along the context
+constexpr int kAttnMaxGroup = 16;       // query heads per kv head, at most
+
+// Workspace carve-up (byte offsets from a 256-byte aligned base).
+struct AttnWorkspace {
+  size_t hdr;       // int32[64]:  [0] number of (seq, chunk) entries, [1] work counter
+  size_t seq_off;   // int32[C+1]: first list entry of every sequence
+  size_t list;      // int2[max_list]: (seq, chunk)
+  size_t ml;        // float2[max_list*Hkv*g]: running max (log2 domain) and sum of weights
+  size_t acc;       // float[max_list*Hkv*g*D]: un-normalised weighted value sums
+  size_t total;
+  int64_t max_list;
+};
+AttnWorkspace attn_workspace_layout(int C, int Hq, int Hkv, int D, int page_size, int max_pages);
+
+int launch_decode_attn(const void* q, const void* k_cache, const void* v_cache,
+                       const int32_t* block_table, const int32_t* ctx_len, void* out, float* lse,
+                       void* workspace, int C, int Hq, int Hkv, int D, int page_size,
+                       int max_pages, float scale, int dtype, hipStream_t stream);
+
+// ---- LM head ----------------------------------------------------------------
+struct LmWorkspace {
+  size_t part;      // LmPartial[C * n_tiles]
+  size_t total;
+  int n_tiles;
+};
+LmWorkspace lm_workspace_layout(int C, int H, int V);
+
+int launch_lmhead_logprob(const void* hidden, const void* weight, const int64_t* seq_id,
+                          const int32_t* step, uint64_t seed, float temperature, int32_t* token,
+                          float* logprob, float* lse, void* workspace, int C, int H, int V,
+                          int dtype, hipStream_t stream);
+
+// ---- IS ratio ---------------------------------------------------------------
+int launch_is_ratio(const float* logp_cur, const float* logp_buf, const float* logp_roll,
+                    const int32_t* cu_seqlens, const int32_t* split, const uint8_t* mask,
+                    float eps_low, float eps_high, float* ratio, float* ratio_clipped,
+                    float* seq_sum, int32_t* seq_cnt, int32_t* seq_nclip, int B,
+                    hipStream_t stream);
+
+}  // namespace copris

@@ -1,0 +1,520 @@
+// Paged-KV grouped-query decode attention for gfx950, split along the context.
+//
+//   worklist kernel   ctx_len -> compact list of (sequence, 512-token chunk) entries
+//   split kernel      one wavefront per (entry, kv head): online-softmax partial
+//                     (running max, weight sum, weighted value sum) for the g query
+//                     heads that share the kv head
+//   merge kernel      per (sequence, kv head): log-sum-exp combination of the
+//                     partials in chunk order, normalisation, store
+//
+// The bf16 split kernel (head_dim 128, page 16) keeps the kernel HBM-bound by doing
+// both contractions on the matrix cores with the TOKENS (scores) or the head
+// dimension (values) as the 16-row M side and the 16-padded group of query heads as
+// the N side:
+//     S^T[token][head] = K_page[token][:] . Q[head][:]          4 x mfma 16x16x32
+//     O^T[d][head]    += V_page^T[d][token] . P^T[token][head]  8 x mfma 16x16x16
+// With that orientation the score tile leaves the first product already in the
+// register layout the second one wants for P^T, and every per-head softmax quantity
+// (max, sum, rescale factor) lives in the lane that owns the head.
+// A (page, kv head) slab is one contiguous 4 KB run: it is fetched with fully
+// coalesced 16-byte loads several pages ahead into registers, parked in LDS with an
+// XOR swizzle, and read back in MFMA operand layout (V through the transposing LDS
+// read).  The physical page order never changes the arithmetic order.
+#include <type_traits>
+
+#include "copris_device.h"
+#include "copris_internal.h"
+
+namespace copris {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+
+// --------------------------------------------------------------------------
+// workspace
+// --------------------------------------------------------------------------
+static inline size_t align256(size_t x) { return (x + 255) & ~static_cast<size_t>(255); }
+
+AttnWorkspace attn_workspace_layout(int C, int Hq, int Hkv, int D, int page_size, int max_pages) {
+  AttnWorkspace w{};
+  const int g = Hq / Hkv;
+  const int64_t max_tokens = static_cast<int64_t>(max_pages) * page_size;
+  const int64_t chunks = (max_tokens + kAttnChunkTokens - 1) / kAttnChunkTokens;
+  w.max_list = static_cast<int64_t>(C) * (chunks > 0 ? chunks : 1);
+  size_t off = 0;
+  w.hdr = off;      off = align256(off + 64 * sizeof(int32_t));
+  w.seq_off = off;  off = align256(off + (static_cast<size_t>(C) + 1) * sizeof(int32_t));
+  w.list = off;     off = align256(off + static_cast<size_t>(w.max_list) * sizeof(int2));
+  w.ml = off;       off = align256(off + static_cast<size_t>(w.max_list) * Hkv * g * sizeof(float2));
+  w.acc = off;      off = align256(off + static_cast<size_t>(w.max_list) * Hkv * g * D * sizeof(float));
+  w.total = off;
+  return w;
+}
+
+// --------------------------------------------------------------------------
+// a1: work list.  One workgroup; sequences in blocks of 1024 with a carried offset.
+// --------------------------------------------------------------------------
+constexpr int kListThreads = 1024;
+
+__global__ __launch_bounds__(kListThreads) void attn_worklist_kernel(
+    const int32_t* __restrict__ ctx_len, int C, int max_tokens, int32_t* __restrict__ hdr,
+    int32_t* __restrict__ seq_off, int2* __restrict__ list) {
+  __shared__ int s_wave[kListThreads / kWave];
+  __shared__ int s_carry;
+  const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
+  if (tid == 0) s_carry = 0;
+  __syncthreads();
+  for (int base = 0; base < C; base += kListThreads) {
+    const int i = base + tid;
+    int n = i < C ? ctx_len[i] : 0;
+    n = n < 0 ? 0 : (n > max_tokens ? max_tokens : n);
+    const int nch = (n + kAttnChunkTokens - 1) / kAttnChunkTokens;
+    int incl = nch;   // inclusive scan inside the wave
+#pragma unroll
+    for (int o = 1; o < kWave; o <<= 1) {
+      const int up = __shfl_up(incl, o, kWave);
+      if (lane >= o) incl += up;
+    }
+    if (lane == kWave - 1) s_wave[wave] = incl;
+    __syncthreads();
+    int before = s_carry;
+    for (int w = 0; w < wave; ++w) before += s_wave[w];
+    const int excl = before + incl - nch;
+    if (i < C) {
+      seq_off[i] = excl;
+      for (int c = 0; c < nch; ++c) list[excl + c] = make_int2(i, c);
+    }
+    __syncthreads();
+    if (tid == kListThreads - 1) s_carry = before + incl;
+    __syncthreads();
+  }
+  if (tid == 0) {
+    seq_off[C] = s_carry;
+    hdr[0] = s_carry;
+    hdr[1] = 0;
+  }
+}
+
+// --------------------------------------------------------------------------
+// a2 (generic): fp32 or bf16, any head_dim in {64,128}, any page size.  One
+// workgroup of 256 threads per (entry, kv head); tokens in tiles of 256.
+// --------------------------------------------------------------------------
+template <typename T> struct Elem;
+template <> struct Elem<float> {
+  static __device__ __forceinline__ float load(const float* p) { return *p; }
+};
+template <> struct Elem<uint16_t> {
+  static __device__ __forceinline__ float load(const uint16_t* p) { return bf16_to_f32(*p); }
+};
+
+template <typename T, int D>
+__global__ __launch_bounds__(256) void attn_split_generic_kernel(
+    const T* __restrict__ q, const T* __restrict__ k_cache, const T* __restrict__ v_cache,
+    const int32_t* __restrict__ block_table, const int32_t* __restrict__ ctx_len,
+    const int32_t* __restrict__ hdr, const int2* __restrict__ list, float2* __restrict__ ws_ml,
+    float* __restrict__ ws_acc, int Hq, int Hkv, int g, int page_size, int max_pages,
+    int max_tokens, float scale_log2e) {
+  constexpr int NT = 256;
+  constexpr int NP = NT / D;                 // token-parallel parts in the value pass
+  __shared__ float s_q[kAttnMaxGroup][D];
+  __shared__ float s_p[kAttnMaxGroup * NT];  // weights of the tile; reused for the part sums
+  __shared__ float s_red[kAttnMaxGroup][NT / kWave];
+  const int item = blockIdx.x;
+  if (item >= hdr[0] * Hkv) return;
+  const int li = item / Hkv, kvh = item - li * Hkv;
+  const int seq = list[li].x, chunk = list[li].y;
+  int n = ctx_len[seq];
+  n = n > max_tokens ? max_tokens : n;
+  const int t0 = chunk * kAttnChunkTokens;
+  const int t1 = min(n, t0 + kAttnChunkTokens);
+  const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
+
+  for (int e = tid; e < g * D; e += NT)
+    s_q[e / D][e % D] = Elem<T>::load(q + (static_cast<size_t>(seq) * Hq + kvh * g) * D + e);
+  __syncthreads();
+
+  float m_run[kAttnMaxGroup], l_run[kAttnMaxGroup], acc[kAttnMaxGroup];
+#pragma unroll
+  for (int h = 0; h < kAttnMaxGroup; ++h) { m_run[h] = -INFINITY; l_run[h] = 0.0f; acc[h] = 0.0f; }
+  const int d_own = tid % D, part = tid / D;
+  const int32_t* bt = block_table + static_cast<size_t>(seq) * max_pages;
+
+  for (int ts = t0; ts < t1; ts += NT) {
+    const int tt = ts + tid;
+    const bool valid = tt < t1;
+    float s[kAttnMaxGroup];
+#pragma unroll
+    for (int h = 0; h < kAttnMaxGroup; ++h) s[h] = 0.0f;
+    if (valid) {
+      const int page = bt[tt / page_size], slot = tt % page_size;
+      const T* krow = k_cache + ((static_cast<size_t>(page) * Hkv + kvh) * page_size + slot) * D;
+      for (int d = 0; d < D; ++d) {
+        const float kv = Elem<T>::load(krow + d);
+#pragma unroll
+        for (int h = 0; h < kAttnMaxGroup; ++h)
+          if (h < g) s[h] = fmaf(s_q[h][d], kv, s[h]);
+      }
+    }
+#pragma unroll
+    for (int h = 0; h < kAttnMaxGroup; ++h) {
+      if (h < g) {
+        s[h] = valid ? s[h] * scale_log2e : -INFINITY;
+        const float wm = wave_max(s[h]);
+        if (lane == 0) s_red[h][wave] = wm;
+      }
+    }
+    __syncthreads();
+    float alpha[kAttnMaxGroup];
+#pragma unroll
+    for (int h = 0; h < kAttnMaxGroup; ++h) {
+      alpha[h] = 1.0f;
+      if (h < g) {
+        float mt = s_red[h][0];
+#pragma unroll
+        for (int w = 1; w < NT / kWave; ++w) mt = fmaxf(mt, s_red[h][w]);
+        const float m_new = fmaxf(m_run[h], mt);
+        alpha[h] = __builtin_amdgcn_exp2f(m_run[h] - m_new);
+        m_run[h] = m_new;
+        const float p = valid ? __builtin_amdgcn_exp2f(s[h] - m_new) : 0.0f;
+        s_p[h * NT + tid] = p;
+        s[h] = p;
+      }
+    }
+    __syncthreads();   // s_red consumed, s_p complete
+#pragma unroll
+    for (int h = 0; h < kAttnMaxGroup; ++h) {
+      if (h < g) {
+        const float ws = wave_sum(s[h]);
+        if (lane == 0) s_red[h][wave] = ws;
+      }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int h = 0; h < kAttnMaxGroup; ++h) {
+      if (h < g) {
+        float lt = s_red[h][0];
+#pragma unroll
+        for (int w = 1; w < NT / kWave; ++w) lt += s_red[h][w];
+        l_run[h] = l_run[h] * alpha[h] + lt;
+        acc[h] *= alpha[h];
+      }
+    }
+    const int ntile = min(NT, t1 - ts);
+    for (int t2 = part; t2 < ntile; t2 += NP) {
+      const int tok = ts + t2;
+      const int page = bt[tok / page_size], slot = tok % page_size;
+      const float vv = Elem<T>::load(
+          v_cache + ((static_cast<size_t>(page) * Hkv + kvh) * page_size + slot) * D + d_own);
+#pragma unroll
+      for (int h = 0; h < kAttnMaxGroup; ++h)
+        if (h < g) acc[h] = fmaf(s_p[h * NT + t2], vv, acc[h]);
+    }
+    __syncthreads();   // before the next tile overwrites s_p / s_red
+  }
+
+  // sum the token-parallel parts in a fixed order: s_p viewed as [NP][16][D]
+#pragma unroll
+  for (int h = 0; h < kAttnMaxGroup; ++h)
+    if (h < g) s_p[(part * kAttnMaxGroup + h) * D + d_own] = acc[h];
+  __syncthreads();
+  if (part == 0) {
+#pragma unroll
+    for (int h = 0; h < kAttnMaxGroup; ++h) {
+      if (h < g) {
+        float a = 0.0f;
+#pragma unroll
+        for (int pp = 0; pp < NP; ++pp) a += s_p[(pp * kAttnMaxGroup + h) * D + d_own];
+        ws_acc[(static_cast<size_t>(item) * g + h) * D + d_own] = a;
+      }
+    }
+  }
+  if (tid == 0) {
+#pragma unroll
+    for (int h = 0; h < kAttnMaxGroup; ++h)
+      if (h < g) ws_ml[static_cast<size_t>(item) * g + h] = make_float2(m_run[h], l_run[h]);
+  }
+}
+
+// --------------------------------------------------------------------------
+// a2 (tuned): bf16, head_dim 128, page 16, g <= 16.  One wavefront per workgroup;
+// wavefronts pull (entry, kv head) items from a counter until the list is empty.
+// --------------------------------------------------------------------------
+constexpr int kD = 128;
+constexpr int kP = 16;
+constexpr int kPageGranules = kP * kD * 2 / 16;   // 256 16-byte granules per (page, kv head)
+
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+  uint32_t r;
+  asm("v_cvt_pk_bf16_f32 %0, %1, %2" : "=v"(r) : "v"(lo), "v"(hi));
+  return r;
+}
+
+struct PageRegs {
+  u32x4 k[4];
+  u32x4 v[4];
+};
+
+__device__ __forceinline__ void load_page(PageRegs& r, const u32x4* __restrict__ kc,
+                                          const u32x4* __restrict__ vc, int page, int Hkv, int kvh,
+                                          int lane) {
+  const size_t base = (static_cast<size_t>(page) * Hkv + kvh) * kPageGranules + lane;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) r.k[i] = kc[base + i * 64];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) r.v[i] = vc[base + i * 64];
+}
+
+// LDS position (in 16-byte granules) of granule c of token row `row`.
+__device__ __forceinline__ int swz_k(int row, int c) { return row * 16 + (c ^ (row & 15)); }
+__device__ __forceinline__ int swz_v(int row, int c) { return row * 16 + (c ^ ((row & 7) << 1)); }
+
+template <int NS>
+__global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2))) void attn_split_mfma_kernel(
+    const uint16_t* __restrict__ q, const u32x4* __restrict__ k_cache,
+    const u32x4* __restrict__ v_cache, const int32_t* __restrict__ block_table,
+    const int32_t* __restrict__ ctx_len, int32_t* __restrict__ hdr, const int2* __restrict__ list,
+    float2* __restrict__ ws_ml, float* __restrict__ ws_acc, int Hq, int Hkv, int g, int max_pages,
+    int max_tokens, float scale_log2e) {
+  __shared__ u32x4 lds_k[kPageGranules];
+  __shared__ u32x4 lds_v[kPageGranules];
+  const int lane = threadIdx.x;
+  const int head = lane & 15;     // N index of both products: the query head of the group
+  const int b = lane >> 4;        // k-group of the MFMA operand layouts
+  const int n_items = hdr[0] * Hkv;
+
+  while (true) {
+    int item = 0;
+    if (lane == 0) item = atomicAdd(&hdr[1], 1);
+    item = __builtin_amdgcn_readfirstlane(item);
+    if (item >= n_items) break;
+    const int li = item / Hkv, kvh = item - li * Hkv;
+    const int seq = list[li].x, chunk = list[li].y;
+    int n = ctx_len[seq];
+    n = n > max_tokens ? max_tokens : n;
+    const int t0 = chunk * kAttnChunkTokens;
+    const int t1 = min(n, t0 + kAttnChunkTokens);
+    const int npg = (t1 - t0 + kP - 1) / kP;          // 1..32 pages
+    const int my_page =
+        lane < npg ? block_table[static_cast<size_t>(seq) * max_pages + t0 / kP + lane] : 0;
+
+    // Q^T operand: lane (head, b) holds Q[head][32*kk + 8*b .. +8]; padded heads are zero
+    bf16x8 qf[4];
+    {
+      const u32x4* qrow =
+          reinterpret_cast<const u32x4*>(q + (static_cast<size_t>(seq) * Hq + kvh * g + head) * kD);
+#pragma unroll
+      for (int kk = 0; kk < 4; ++kk) {
+        u32x4 x = {0u, 0u, 0u, 0u};
+        if (head < g) x = qrow[kk * 4 + b];
+        qf[kk] = __builtin_bit_cast(bf16x8, x);
+      }
+    }
+
+    float m_run = -INFINITY, l_run = 0.0f;
+    f32x4 o[8];
+#pragma unroll
+    for (int dt = 0; dt < 8; ++dt) o[dt] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+
+    // One page: park it in LDS, refill its registers with the page NS ahead, then
+    // both products.  `pp` is the page's index inside the chunk (wave-uniform).
+    // `steady`: the page NS ahead exists and this page is full, so the refill is
+    // unconditional (which lets the compiler count outstanding loads exactly and keep
+    // the younger stages in flight) and no masking is needed.
+    auto do_page = [&](PageRegs& r, const int pp, auto steady) __attribute__((always_inline)) {
+      constexpr bool kSteady = decltype(steady)::value;
+      // granule (i*64+lane) = token row 4i+b, column granule `head`
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        lds_k[swz_k(4 * i + b, head)] = r.k[i];
+        lds_v[swz_v(4 * i + b, head)] = r.v[i];
+      }
+      if (kSteady || pp + NS < npg)
+        load_page(r, k_cache, v_cache, __builtin_amdgcn_readlane(my_page, pp + NS), Hkv, kvh, lane);
+      __syncthreads();
+
+      // S^T[token][head]: A = K rows (token = lane&15), B = Q^T
+      f32x4 sc = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+      for (int kk = 0; kk < 4; ++kk) {
+        const bf16x8 kf = __builtin_bit_cast(bf16x8, lds_k[swz_k(head, 4 * kk + b)]);
+        sc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf, qf[kk], sc, 0, 0, 0);
+      }
+      // this lane: head `head`, tokens 4b..4b+3 of the page
+      const int valid = t1 - t0 - pp * kP;   // tokens of this page inside the context
+      float t[4];
+#pragma unroll
+      for (int rr = 0; rr < 4; ++rr) t[rr] = sc[rr] * scale_log2e;
+      if (!kSteady && valid < kP) {
+#pragma unroll
+        for (int rr = 0; rr < 4; ++rr) t[rr] = (4 * b + rr < valid) ? t[rr] : -INFINITY;
+      }
+      float mx = fmaxf(fmaxf(t[0], t[1]), fmaxf(t[2], t[3]));
+      mx = fmaxf(mx, __shfl_xor(mx, 16, kWave));
+      mx = fmaxf(mx, __shfl_xor(mx, 32, kWave));
+      const float m_new = fmaxf(m_run, mx);
+      const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+      m_run = m_new;
+      float p[4];
+#pragma unroll
+      for (int rr = 0; rr < 4; ++rr) p[rr] = __builtin_amdgcn_exp2f(t[rr] - m_new);
+      l_run = l_run * alpha + ((p[0] + p[1]) + (p[2] + p[3]));
+      const uint2 pk = make_uint2(pack_bf16x2(p[0], p[1]), pack_bf16x2(p[2], p[3]));
+      const s16x4 pf = __builtin_bit_cast(s16x4, pk);
+      if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {
+#pragma unroll
+        for (int dt = 0; dt < 8; ++dt) o[dt] *= alpha;
+      }
+      // O^T[d][head] += V^T[d][token] P^T[token][head]: A = V^T via the transposing
+      // read (lane supplies row 4b + L/4, columns 16dt + 4(L%4)..+3, L = lane&15)
+      const int vrow = 4 * b + (head >> 2);
+      const char* vbase = reinterpret_cast<const char*>(lds_v) + (head & 1) * 8;
+#pragma unroll
+      for (int dt = 0; dt < 8; ++dt) {
+        const char* addr = vbase + swz_v(vrow, 2 * dt + ((head & 3) >> 1)) * 16;
+        s16x4 vf = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+            (__attribute__((address_space(3))) s16x4*)(addr));
+        if (!kSteady && valid < kP) {   // rows past the context may hold anything (NaN): zero them
+#pragma unroll
+          for (int rr = 0; rr < 4; ++rr)
+            vf[rr] = (4 * b + rr < valid) ? vf[rr] : static_cast<short>(0);
+        }
+        o[dt] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(vf, pf, o[dt], 0, 0, 0);
+      }
+      __syncthreads();   // the next page may overwrite the LDS tiles
+    };
+
+    static_assert(NS == 3, "the page pipeline below is written out for three stages");
+    PageRegs st0, st1, st2;
+    int p0 = 0;
+    load_page(st0, k_cache, v_cache, __builtin_amdgcn_readlane(my_page, 0), Hkv, kvh, lane);
+    if (npg >= 2 * NS) {
+      load_page(st1, k_cache, v_cache, __builtin_amdgcn_readlane(my_page, 1), Hkv, kvh, lane);
+      load_page(st2, k_cache, v_cache, __builtin_amdgcn_readlane(my_page, 2), Hkv, kvh, lane);
+      do {   // steady state: every refill exists, every page is full
+        do_page(st0, p0, std::true_type{});
+        do_page(st1, p0 + 1, std::true_type{});
+        do_page(st2, p0 + 2, std::true_type{});
+        p0 += NS;
+      } while (p0 + 2 * NS <= npg);
+    } else {
+      if (1 < npg) load_page(st1, k_cache, v_cache, __builtin_amdgcn_readlane(my_page, 1), Hkv, kvh, lane);
+      if (2 < npg) load_page(st2, k_cache, v_cache, __builtin_amdgcn_readlane(my_page, 2), Hkv, kvh, lane);
+    }
+    for (; p0 < npg; p0 += NS) {   // the last 3..5 pages of the chunk (or a short chunk)
+      do_page(st0, p0, std::false_type{});
+      if (p0 + 1 < npg) do_page(st1, p0 + 1, std::false_type{});
+      if (p0 + 2 < npg) do_page(st2, p0 + 2, std::false_type{});
+    }
+
+    // partial results of this item: lane (head, b) owns d = 16dt + 4b + r
+    l_run += __shfl_xor(l_run, 16, kWave);
+    l_run += __shfl_xor(l_run, 32, kWave);
+    if (head < g) {
+      float* dst = ws_acc + (static_cast<size_t>(item) * g + head) * kD + 4 * b;
+#pragma unroll
+      for (int dt = 0; dt < 8; ++dt)
+        *reinterpret_cast<float4*>(dst + 16 * dt) = make_float4(o[dt][0], o[dt][1], o[dt][2], o[dt][3]);
+      if (b == 0) ws_ml[static_cast<size_t>(item) * g + head] = make_float2(m_run, l_run);
+    }
+  }
+}
+
+// --------------------------------------------------------------------------
+// a3: merge.  One workgroup per (sequence, kv head), one thread per head_dim index.
+// --------------------------------------------------------------------------
+template <typename T> __device__ __forceinline__ void store_out(T* p, float v);
+template <> __device__ __forceinline__ void store_out<float>(float* p, float v) { *p = v; }
+template <> __device__ __forceinline__ void store_out<uint16_t>(uint16_t* p, float v) { *p = f32_to_bf16(v); }
+
+template <typename T>
+__global__ void attn_merge_kernel(const int32_t* __restrict__ seq_off,
+                                  const float2* __restrict__ ws_ml,
+                                  const float* __restrict__ ws_acc, T* __restrict__ out,
+                                  float* __restrict__ lse, int Hq, int Hkv, int g, int D) {
+  const int seq = blockIdx.x, kvh = blockIdx.y, d = threadIdx.x;
+  const int e0 = seq_off[seq], e1 = seq_off[seq + 1];
+  for (int h = 0; h < g; ++h) {
+    float m_star = -INFINITY;
+    for (int e = e0; e < e1; ++e)
+      m_star = fmaxf(m_star, ws_ml[(static_cast<size_t>(e) * Hkv + kvh) * g + h].x);
+    float denom = 0.0f, num = 0.0f;
+    for (int e = e0; e < e1; ++e) {
+      const size_t slot = (static_cast<size_t>(e) * Hkv + kvh) * g + h;
+      const float2 ml = ws_ml[slot];
+      const float w = __builtin_amdgcn_exp2f(ml.x - m_star);
+      denom = fmaf(w, ml.y, denom);
+      num = fmaf(w, ws_acc[slot * D + d], num);
+    }
+    const size_t oh = static_cast<size_t>(seq) * Hq + kvh * g + h;
+    store_out<T>(out + oh * D + d, e1 > e0 ? num / denom : 0.0f);
+    if (lse != nullptr && d == 0)
+      lse[oh] = e1 > e0 ? (m_star + __builtin_amdgcn_logf(denom)) * kLn2 : -INFINITY;
+  }
+}
+
+// --------------------------------------------------------------------------
+// host launcher
+// --------------------------------------------------------------------------
+int launch_decode_attn(const void* q, const void* k_cache, const void* v_cache,
+                       const int32_t* block_table, const int32_t* ctx_len, void* out, float* lse,
+                       void* workspace, int C, int Hq, int Hkv, int D, int page_size,
+                       int max_pages, float scale, int dtype, hipStream_t stream) {
+  const int g = Hq / Hkv;
+  const AttnWorkspace w = attn_workspace_layout(C, Hq, Hkv, D, page_size, max_pages);
+  char* ws = static_cast<char*>(workspace);
+  int32_t* hdr = reinterpret_cast<int32_t*>(ws + w.hdr);
+  int32_t* seq_off = reinterpret_cast<int32_t*>(ws + w.seq_off);
+  int2* list = reinterpret_cast<int2*>(ws + w.list);
+  float2* ws_ml = reinterpret_cast<float2*>(ws + w.ml);
+  float* ws_acc = reinterpret_cast<float*>(ws + w.acc);
+  const int64_t max_tokens64 = static_cast<int64_t>(max_pages) * page_size;
+  const int max_tokens = static_cast<int>(max_tokens64);
+  const float scale_log2e = scale * kLog2e;
+
+  hipLaunchKernelGGL(attn_worklist_kernel, dim3(1), dim3(kListThreads), 0, stream, ctx_len, C,
+                     max_tokens, hdr, seq_off, list);
+  COPRIS_CHECK_LAUNCH("attn_worklist_kernel");
+
+  const int64_t max_items = w.max_list * Hkv;
+  const bool tuned = dtype == 1 && D == kD && page_size == kP;
+  if (tuned) {
+    constexpr int kWavesPerCu = 8;
+    int grid = 256 * kWavesPerCu;
+    if (grid > max_items) grid = static_cast<int>(max_items);
+    hipLaunchKernelGGL(attn_split_mfma_kernel<3>, dim3(grid), dim3(64), 0, stream,
+                       static_cast<const uint16_t*>(q), static_cast<const u32x4*>(k_cache),
+                       static_cast<const u32x4*>(v_cache), block_table, ctx_len, hdr, list, ws_ml,
+                       ws_acc, Hq, Hkv, g, max_pages, max_tokens, scale_log2e);
+    COPRIS_CHECK_LAUNCH("attn_split_mfma_kernel");
+  } else {
+    const dim3 grid(static_cast<unsigned>(max_items));
+#define COPRIS_GENERIC(T, DD)                                                                   \
+  hipLaunchKernelGGL((attn_split_generic_kernel<T, DD>), grid, dim3(256), 0, stream,            \
+                     static_cast<const T*>(q), static_cast<const T*>(k_cache),                  \
+                     static_cast<const T*>(v_cache), block_table, ctx_len, hdr, list, ws_ml,    \
+                     ws_acc, Hq, Hkv, g, page_size, max_pages, max_tokens, scale_log2e)
+    if (dtype == 0 && D == 64) COPRIS_GENERIC(float, 64);
+    else if (dtype == 0 && D == 128) COPRIS_GENERIC(float, 128);
+    else if (dtype == 1 && D == 64) COPRIS_GENERIC(uint16_t, 64);
+    else COPRIS_GENERIC(uint16_t, 128);
+#undef COPRIS_GENERIC
+    COPRIS_CHECK_LAUNCH("attn_split_generic_kernel");
+  }
+
+  if (dtype == 0) {
+    hipLaunchKernelGGL(attn_merge_kernel<float>, dim3(C, Hkv), dim3(D), 0, stream, seq_off, ws_ml,
+                       ws_acc, static_cast<float*>(out), lse, Hq, Hkv, g, D);
+  } else {
+    hipLaunchKernelGGL(attn_merge_kernel<uint16_t>, dim3(C, Hkv), dim3(D), 0, stream, seq_off,
+                       ws_ml, ws_acc, static_cast<uint16_t*>(out), lse, Hq, Hkv, g, D);
+  }
+  COPRIS_CHECK_LAUNCH("attn_merge_kernel");
+  return 0;
+}
+
+}  // namespace copris
