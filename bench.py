@@ -1,0 +1,218 @@
+#!/usr/bin/env python3
+"""Benchmark of the CoPRIS rollout-decode hot path on one MI355X.
+
+One step = one pass of the whole hot path over one batch of seeded synthetic input:
+  copris_decode_attn (work list, split-K attention, merge: one layer's KV) +
+  copris_lmhead_logprob (LM head + log-softmax + Gumbel-max + log-prob gather)
+on the 7B-shaped C=256 decode configuration, + copris_is_ratio on the cross-stage IS
+batch (256 trajectories).  All inputs are resident in HBM before the timed region.
+
+Prints ONE JSON line: decode tokens/s (C / step time), the HBM roofline of the dominant
+kernel (algorithmic bytes / kernel duration measured with events around that kernel's
+launches, vs 8 TB/s) and the fp64 CPU oracle timed on a bounded sample of the same
+workload on this machine's host cores.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16, published
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", type=int, default=2, choices=[0, 1, 2],
+                    help="decode config index (2 = the 7B-shaped C=256 config the metric is quoted on)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample", type=int, default=256, help="sequences in the oracle sample")
+    return ap.parse_args()
+
+
+def algorithmic_bytes(cfg, inp, isb):
+    """Bytes the method itself must move, per launch (the figures the design doc states)."""
+    import numpy as np
+    eb = cfg.elem_bytes
+    ctx = inp["ctx_len"].astype(np.int64)
+    pages = (ctx + cfg.page_size - 1) // cfg.page_size
+    kv = int(ctx.sum()) * 2 * cfg.Hkv * cfg.D * eb            # K and V rows of every context token
+    attn = kv + int(pages.sum()) * 4 + 2 * cfg.C * cfg.Hq * cfg.D * eb   # + block table + q in + out
+    lm = cfg.V * cfg.H * eb + cfg.C * cfg.H * eb + 12 * cfg.C  # W once + hidden + token/logprob/lse
+    is_ = 17 * int(isb["N"])                                    # cur + selected old + mask in, 2 outputs
+    return {"attn": attn, "lm": lm, "is": is_, "kv": kv}
+
+
+def cpu_baseline(cfg, inp, n_sample):
+    """The fp64 oracle, as it stands, on the first n_sample sequences of the same workload."""
+    import numpy as np
+    from threadpoolctl import threadpool_info
+    from oracle import copris_oracle as O
+    from paper_2511_05589_amd import workloads as W
+
+    seqs = np.arange(min(n_sample, cfg.C))
+    P = cfg.page_size
+    npg = (inp["ctx_len"][seqs].astype(np.int64) + P - 1) // P
+    pages = np.concatenate([inp["block_table"][s, :n] for s, n in zip(seqs, npg)])
+    bt = np.full((len(seqs), int(npg.max())), -1, dtype=np.int32)
+    off = 0
+    for i, n in enumerate(npg):
+        bt[i, :n] = np.arange(off, off + n)
+        off += n
+    f = lambda a: W.to_f32(a, cfg.dtype)
+    q, kc, vc = f(inp["q"][seqs]), f(inp["k_cache"][pages]), f(inp["v_cache"][pages])
+    hid, wt = f(inp["hidden"][seqs]), f(inp["weight"])
+    # whole passes over the sample until about 10 s of CPU work have been timed
+    t_attn = t_lm = 0.0
+    passes = 0
+    while passes == 0 or (t_attn + t_lm < 10.0 and passes < 20):
+        t0 = time.perf_counter()
+        O.decode_attn(q, kc, vc, bt, inp["ctx_len"][seqs], inp["scale"])
+        t1 = time.perf_counter()
+        O.lmhead_logprob(hid, wt, inp["seq_id"][seqs], inp["step"][seqs], inp["seed"], inp["temperature"])
+        t2 = time.perf_counter()
+        t_attn += t1 - t0
+        t_lm += t2 - t1
+        passes += 1
+    threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    total = t_attn + t_lm
+    return {"value": round(len(seqs) * passes / total, 2), "unit": "tokens/s", "cores": int(threads),
+            "kind": "oracle",
+            "sample": (f"first {len(seqs)} of {cfg.C} sequences of the same workload, {passes} pass(es): "
+                       f"oracle attention over their full contexts ({t_attn / passes:.2f} s/pass) + oracle LM "
+                       f"head / sampling for their rows incl. widening W to fp64 ({t_lm / passes:.2f} s/pass); "
+                       f"numpy fp64, BLAS threads {threads}, {len(os.sched_getaffinity(0))} cores visible"),
+            "seconds": round(total, 3)}
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no sharding, no collectives); "
+              f"--gpus {args.gpus} is not supported", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2511_05589_amd import binding, runner, workloads as W
+
+    dev = runner.require_gpu()
+    cfg = W.DECODE_CONFIGS[args.config]
+    t_gen = time.perf_counter()
+    inp = W.make_decode_inputs(cfg)
+    isb = W.make_is_inputs(W.IS_CONFIGS[4 if args.config != 0 else 0])
+    t_gen = time.perf_counter() - t_gen
+
+    attn = runner.stage_attn(inp, cfg.dtype, dev)
+    lm = runner.stage_lmhead(inp, cfg.dtype, dev)
+    isd = runner.stage_is_ratio(isb, dev)
+    stream = torch.cuda.current_stream()
+    ab = algorithmic_bytes(cfg, inp, isb)
+
+    def step():
+        attn.run(stream)
+        lm.run(stream)
+        isd.run(stream)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+
+    # ---- timed region: exactly K steps, events around each of the three calls ----
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(args.steps):
+        ev[k][0].record(stream)
+        attn.run(stream)
+        ev[k][1].record(stream)
+        lm.run(stream)
+        ev[k][2].record(stream)
+        isd.run(stream)
+        ev[k][3].record(stream)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_per_step = wall * 1e3 / args.steps
+    call_ms = {name: float(np.mean([ev[k][i].elapsed_time(ev[k][i + 1]) for k in range(args.steps)]))
+               for i, name in enumerate(["attn", "lm", "is"])}
+
+    # ---- per-kernel durations: the library's launch hook records an event before and
+    # after every kernel launch (same stream, same K steps, instrumented pass) ----
+    recs = []
+
+    def hook(kernel, phase, _stream, _user):
+        e = torch.cuda.Event(enable_timing=True)
+        e.record(stream)
+        recs.append((kernel.decode(), phase, e))
+
+    binding.set_launch_hook(hook)
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    binding.set_launch_hook(None)
+    kernel_ms = {}
+    for i in range(0, len(recs), 2):
+        (name, p0, e0), (name1, p1, e1) = recs[i], recs[i + 1]
+        assert name == name1 and p0 == 0 and p1 == 1
+        kernel_ms.setdefault(name, []).append(e0.elapsed_time(e1))
+    kernel_ms = {k: float(np.mean(v)) for k, v in kernel_ms.items()}
+
+    # ---- roofline of the dominant kernel ----
+    main_kernels = {"attn": next(k for k in kernel_ms if k.startswith("attn_split")),
+                    "lm": next(k for k in kernel_ms if k.startswith("lmhead") and "merge" not in k),
+                    "is": "is_ratio_kernel"}
+    traffic = {}
+    tpath = os.path.join(ROOT, "profiles", "traffic.json")
+    if os.path.exists(tpath):
+        traffic = json.load(open(tpath)).get(f"config{args.config}", {})
+    kernels = {}
+    for part, kname in main_kernels.items():
+        gbs = ab[part] / (kernel_ms[kname] * 1e-3) / 1e9
+        kernels[kname] = {"avg_ms": round(kernel_ms[kname], 4), "algorithmic_bytes": ab[part],
+                          "achieved_GBps": round(gbs, 1), "frac_hbm": round(gbs / HBM_PEAK_GBS, 4),
+                          "traffic": traffic.get(kname)}
+    lm_flops = 2.0 * cfg.C * cfg.H * cfg.V
+    kernels[main_kernels["lm"]]["mfma_frac"] = round(
+        lm_flops / (kernel_ms[main_kernels["lm"]] * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4)
+    dom = max((main_kernels["attn"], main_kernels["lm"]), key=lambda k: kernel_ms[k])
+    roofline = {"bound": "hbm", "kernel": dom, "achieved": kernels[dom]["achieved_GBps"],
+                "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": kernels[dom]["frac_hbm"],
+                "traffic": kernels[dom]["traffic"], "avg_kernel_ms": kernels[dom]["avg_ms"]}
+    pair_gbs = (ab["attn"] + ab["lm"]) / ((call_ms["attn"] + call_ms["lm"]) * 1e-3) / 1e9
+
+    result = {
+        "metric": "decode tokens/s at fixed concurrency C; achieved HBM GB/s vs MI355X peak",
+        "value": round(cfg.C / (ms_per_step * 1e-3), 1), "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16" if cfg.dtype == W.BF16 else "f32", "data": "synthetic",
+        "config": {"workload": f"config {cfg.index} ({cfg.name}): C={cfg.C}, {cfg.Hq}q/{cfg.Hkv}kv heads, "
+                               f"head_dim {cfg.D}, page {cfg.page_size}, mean ctx {inp['ctx_len'].mean():.0f}, "
+                               f"LM head {cfg.H}x{cfg.V}; + IS batch of {isb['B']} trajectories, {isb['N']} tokens",
+                   "step": "decode_attn (1 layer) + lmhead_logprob + is_ratio", "concurrency": cfg.C},
+        "roofline": roofline,
+        "call_ms": {k: round(v, 4) for k, v in call_ms.items()},
+        "attn_plus_lm": {"algorithmic_GB": round((ab["attn"] + ab["lm"]) / 1e9, 4),
+                         "achieved_GBps": round(pair_gbs, 1), "frac_hbm": round(pair_gbs / HBM_PEAK_GBS, 4),
+                         "decode_tokens_per_s_attn_lm_only": round(cfg.C / ((call_ms["attn"] + call_ms["lm"]) * 1e-3), 1)},
+        "kernels": kernels,
+        "all_kernel_ms": {k: round(v, 4) for k, v in kernel_ms.items()},
+        "input_generation_s": round(t_gen, 1),
+    }
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(cfg, inp, args.cpu_sample)
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

@@ -63,6 +63,14 @@ const char* copris_version(void);
  * and the HIP runtime's error text (thread-local storage, host pointer, "" if none). */
 const char* copris_last_error_detail(void);
 
+/* Profiling aid.  While a hook is set, every kernel launch of the library calls it on
+ * the launching host thread, before (phase 0) and after (phase 1) the launch is
+ * enqueued, with the kernel's name and the stream: a caller can record events there
+ * to time individual kernels.  Process-wide, not thread-safe against concurrent
+ * calls; pass NULL to remove it.  The hook must not call back into the library. */
+typedef void (*copris_launch_hook_fn)(const char* kernel, int phase, void* stream, void* user);
+void copris_set_launch_hook(copris_launch_hook_fn hook, void* user);
+
 /* ------------------------------------------------------------------------
  * Paged-KV grouped-query decode attention.
  *

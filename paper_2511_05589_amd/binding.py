@@ -27,6 +27,7 @@ SIGNATURES = {
     "copris_strerror": (c_char_p, [c_int]),
     "copris_version": (c_char_p, []),
     "copris_last_error_detail": (c_char_p, []),
+    "copris_set_launch_hook": (None, [c_void_p, c_void_p]),
     "copris_decode_attn_workspace_bytes": (c_size_t, [c_int] * 6),
     "copris_decode_attn": (c_int, [c_void_p] * 8 + [c_size_t] + [c_int] * 6 + [c_int64, c_float, c_int, c_void_p]),
     "copris_lmhead_logprob_workspace_bytes": (c_size_t, [c_int] * 3),
@@ -75,6 +76,22 @@ def strerror(code: int) -> str:
 
 def version() -> str:
     return load_library().copris_version().decode()
+
+
+LAUNCH_HOOK = ctypes.CFUNCTYPE(None, c_char_p, c_int, c_void_p, c_void_p)
+_hook_ref = None
+
+
+def set_launch_hook(fn) -> None:
+    """fn(kernel: bytes, phase: int, stream: int|None, user) or None to remove the hook."""
+    global _hook_ref
+    lib = load_library()
+    if fn is None:
+        lib.copris_set_launch_hook(None, None)
+        _hook_ref = None
+        return
+    _hook_ref = LAUNCH_HOOK(fn)           # keep the trampoline alive
+    lib.copris_set_launch_hook(ctypes.cast(_hook_ref, c_void_p), None)
 
 
 def _ptr(t) -> Optional[int]:

@@ -11,6 +11,8 @@ inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 
 inline bool aligned256(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 255u) == 0; }
 
 thread_local char g_detail[256] = "";
+copris_launch_hook_fn g_hook = nullptr;
+void* g_hook_user = nullptr;
 
 bool attn_shape_ok(int C, int Hq, int Hkv, int D, int page_size, int max_pages) {
   if (C <= 0 || Hq <= 0 || Hkv <= 0 || D <= 0 || page_size <= 0 || max_pages <= 0) return false;
@@ -39,6 +41,9 @@ bool launch_ok(const char* kernel_name) {
            hipGetErrorString(e));
   return false;
 }
+void launch_hook(const char* kernel_name, int phase, hipStream_t stream) {
+  if (g_hook != nullptr) g_hook(kernel_name, phase, static_cast<void*>(stream), g_hook_user);
+}
 }  // namespace copris
 
 extern "C" {
@@ -57,6 +62,11 @@ const char* copris_strerror(int code) {
 const char* copris_version(void) { return "0.1.0"; }
 
 const char* copris_last_error_detail(void) { return g_detail; }
+
+void copris_set_launch_hook(copris_launch_hook_fn hook, void* user) {
+  g_hook = hook;
+  g_hook_user = user;
+}
 
 size_t copris_decode_attn_workspace_bytes(int C, int Hq, int Hkv, int D, int page_size,
                                           int max_pages) {

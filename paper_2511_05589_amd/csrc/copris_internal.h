@@ -9,10 +9,16 @@ namespace copris {
 // Checks hipGetLastError() after a launch; on failure records "<kernel>: <hip error>" for
 // copris_last_error_detail() and returns false.
 bool launch_ok(const char* kernel_name);
+// Calls the profiling hook (if one is set) before (phase 0) / after (phase 1) a launch.
+void launch_hook(const char* kernel_name, int phase, hipStream_t stream);
 constexpr int kErrLaunch = -4;   // COPRIS_ELAUNCH
-#define COPRIS_CHECK_LAUNCH(name) \
-  do {                            \
-    if (!::copris::launch_ok(name)) return ::copris::kErrLaunch; \
+
+// Around every kernel launch of a launcher whose stream variable is called `stream`.
+#define COPRIS_PRE(name) ::copris::launch_hook(name, 0, stream)
+#define COPRIS_POST(name)                                          \
+  do {                                                             \
+    if (!::copris::launch_ok(name)) return ::copris::kErrLaunch;   \
+    ::copris::launch_hook(name, 1, stream);                        \
   } while (0)
 
 // ---- decode attention -------------------------------------------------------

@@ -425,7 +425,7 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2))) void
 }
 
 // --------------------------------------------------------------------------
-// a3: merge.  One workgroup per (sequence, kv head), one thread per head_dim index.
+// a3: merge.  One workgroup per (sequence, query head), one thread per head_dim index.
 // --------------------------------------------------------------------------
 template <typename T> __device__ __forceinline__ void store_out(T* p, float v);
 template <> __device__ __forceinline__ void store_out<float>(float* p, float v) { *p = v; }
@@ -436,25 +436,44 @@ __global__ void attn_merge_kernel(const int32_t* __restrict__ seq_off,
                                   const float2* __restrict__ ws_ml,
                                   const float* __restrict__ ws_acc, T* __restrict__ out,
                                   float* __restrict__ lse, int Hq, int Hkv, int g, int D) {
-  const int seq = blockIdx.x, kvh = blockIdx.y, d = threadIdx.x;
+  // one workgroup per (sequence, query head); thread d owns one head_dim index
+  const int seq = blockIdx.x, hq = blockIdx.y, d = threadIdx.x;
+  const int kvh = hq / g, h = hq - kvh * g;
   const int e0 = seq_off[seq], e1 = seq_off[seq + 1];
-  for (int h = 0; h < g; ++h) {
-    float m_star = -INFINITY;
-    for (int e = e0; e < e1; ++e)
-      m_star = fmaxf(m_star, ws_ml[(static_cast<size_t>(e) * Hkv + kvh) * g + h].x);
-    float denom = 0.0f, num = 0.0f;
-    for (int e = e0; e < e1; ++e) {
-      const size_t slot = (static_cast<size_t>(e) * Hkv + kvh) * g + h;
-      const float2 ml = ws_ml[slot];
-      const float w = __builtin_amdgcn_exp2f(ml.x - m_star);
-      denom = fmaf(w, ml.y, denom);
-      num = fmaf(w, ws_acc[slot * D + d], num);
+  const size_t stride = static_cast<size_t>(Hkv) * g;          // slots per list entry
+  const size_t slot0 = (static_cast<size_t>(e0) * Hkv + kvh) * g + h;
+  const int n = e1 - e0;
+  float m_star = -INFINITY;
+  for (int e = 0; e < n; ++e) m_star = fmaxf(m_star, ws_ml[slot0 + e * stride].x);
+  float denom = 0.0f, num = 0.0f;
+  int e = 0;
+  for (; e + 4 <= n; e += 4) {   // four chunks' loads in flight; summation order stays e = 0, 1, 2, ...
+    float2 ml[4];
+    float a[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const size_t slot = slot0 + (e + u) * stride;
+      ml[u] = ws_ml[slot];
+      a[u] = ws_acc[slot * D + d];
     }
-    const size_t oh = static_cast<size_t>(seq) * Hq + kvh * g + h;
-    store_out<T>(out + oh * D + d, e1 > e0 ? num / denom : 0.0f);
-    if (lse != nullptr && d == 0)
-      lse[oh] = e1 > e0 ? (m_star + __builtin_amdgcn_logf(denom)) * kLn2 : -INFINITY;
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const float w = __builtin_amdgcn_exp2f(ml[u].x - m_star);
+      denom = fmaf(w, ml[u].y, denom);
+      num = fmaf(w, a[u], num);
+    }
   }
+  for (; e < n; ++e) {
+    const size_t slot = slot0 + e * stride;
+    const float2 ml = ws_ml[slot];
+    const float w = __builtin_amdgcn_exp2f(ml.x - m_star);
+    denom = fmaf(w, ml.y, denom);
+    num = fmaf(w, ws_acc[slot * D + d], num);
+  }
+  const size_t oh = static_cast<size_t>(seq) * Hq + hq;
+  store_out<T>(out + oh * D + d, n > 0 ? num / denom : 0.0f);
+  if (lse != nullptr && d == 0)
+    lse[oh] = n > 0 ? (m_star + __builtin_amdgcn_logf(denom)) * kLn2 : -INFINITY;
 }
 
 // --------------------------------------------------------------------------
@@ -476,9 +495,10 @@ int launch_decode_attn(const void* q, const void* k_cache, const void* v_cache,
   const int max_tokens = static_cast<int>(max_tokens64);
   const float scale_log2e = scale * kLog2e;
 
+  COPRIS_PRE("attn_worklist_kernel");
   hipLaunchKernelGGL(attn_worklist_kernel, dim3(1), dim3(kListThreads), 0, stream, ctx_len, C,
                      max_tokens, hdr, seq_off, list);
-  COPRIS_CHECK_LAUNCH("attn_worklist_kernel");
+  COPRIS_POST("attn_worklist_kernel");
 
   const int64_t max_items = w.max_list * Hkv;
   const bool tuned = dtype == 1 && D == kD && page_size == kP;
@@ -486,11 +506,12 @@ int launch_decode_attn(const void* q, const void* k_cache, const void* v_cache,
     constexpr int kWavesPerCu = 8;
     int grid = 256 * kWavesPerCu;
     if (grid > max_items) grid = static_cast<int>(max_items);
+    COPRIS_PRE("attn_split_mfma_kernel");
     hipLaunchKernelGGL(attn_split_mfma_kernel<3>, dim3(grid), dim3(64), 0, stream,
                        static_cast<const uint16_t*>(q), static_cast<const u32x4*>(k_cache),
                        static_cast<const u32x4*>(v_cache), block_table, ctx_len, hdr, list, ws_ml,
                        ws_acc, Hq, Hkv, g, max_pages, max_tokens, scale_log2e);
-    COPRIS_CHECK_LAUNCH("attn_split_mfma_kernel");
+    COPRIS_POST("attn_split_mfma_kernel");
   } else {
     const dim3 grid(static_cast<unsigned>(max_items));
 #define COPRIS_GENERIC(T, DD)                                                                   \
@@ -498,22 +519,24 @@ int launch_decode_attn(const void* q, const void* k_cache, const void* v_cache,
                      static_cast<const T*>(q), static_cast<const T*>(k_cache),                  \
                      static_cast<const T*>(v_cache), block_table, ctx_len, hdr, list, ws_ml,    \
                      ws_acc, Hq, Hkv, g, page_size, max_pages, max_tokens, scale_log2e)
+    COPRIS_PRE("attn_split_generic_kernel");
     if (dtype == 0 && D == 64) COPRIS_GENERIC(float, 64);
     else if (dtype == 0 && D == 128) COPRIS_GENERIC(float, 128);
     else if (dtype == 1 && D == 64) COPRIS_GENERIC(uint16_t, 64);
     else COPRIS_GENERIC(uint16_t, 128);
 #undef COPRIS_GENERIC
-    COPRIS_CHECK_LAUNCH("attn_split_generic_kernel");
+    COPRIS_POST("attn_split_generic_kernel");
   }
 
+  COPRIS_PRE("attn_merge_kernel");
   if (dtype == 0) {
-    hipLaunchKernelGGL(attn_merge_kernel<float>, dim3(C, Hkv), dim3(D), 0, stream, seq_off, ws_ml,
+    hipLaunchKernelGGL(attn_merge_kernel<float>, dim3(C, Hq), dim3(D), 0, stream, seq_off, ws_ml,
                        ws_acc, static_cast<float*>(out), lse, Hq, Hkv, g, D);
   } else {
-    hipLaunchKernelGGL(attn_merge_kernel<uint16_t>, dim3(C, Hkv), dim3(D), 0, stream, seq_off,
+    hipLaunchKernelGGL(attn_merge_kernel<uint16_t>, dim3(C, Hq), dim3(D), 0, stream, seq_off,
                        ws_ml, ws_acc, static_cast<uint16_t*>(out), lse, Hq, Hkv, g, D);
   }
-  COPRIS_CHECK_LAUNCH("attn_merge_kernel");
+  COPRIS_POST("attn_merge_kernel");
   return 0;
 }
 

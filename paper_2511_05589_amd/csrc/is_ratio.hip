@@ -126,6 +126,7 @@ int launch_is_ratio(const float* logp_cur, const float* logp_buf, const float* l
                     hipStream_t stream) {
   if (B == 0) return 0;
   const float lo = 1.0f - eps_low, hi = 1.0f + eps_high;
+  COPRIS_PRE("is_ratio_kernel");
   if (mask != nullptr) {
     hipLaunchKernelGGL(is_ratio_kernel<true>, dim3(B), dim3(kIsThreads), 0, stream, logp_cur,
                        logp_buf, logp_roll, cu_seqlens, split, mask, lo, hi, ratio, ratio_clipped,
@@ -135,7 +136,7 @@ int launch_is_ratio(const float* logp_cur, const float* logp_buf, const float* l
                        logp_buf, logp_roll, cu_seqlens, split, mask, lo, hi, ratio, ratio_clipped,
                        seq_sum, seq_cnt, seq_nclip);
   }
-  COPRIS_CHECK_LAUNCH("is_ratio_kernel");
+  COPRIS_POST("is_ratio_kernel");
   return 0;
 }
 
