@@ -1,6 +1,6 @@
 // C ABI of libcopris: argument checks on the host, then kernel launches on the
 // caller's stream.  No allocation, no synchronisation, no host copies.
-#include "../../include/copris.h"
+#include "copris.h"
 #include "copris_internal.h"
 
 #include <cstdio>

@@ -179,12 +179,12 @@ __global__ __launch_bounds__(256) void lmhead_generic_kernel(
 // i.e. exactly one Philox block (4 words) per run, and the row's running
 // log-sum-exp / arg-max state lives in that lane.
 //
-// A workgroup (4 waves, 2x2) owns a 128 (vocab) x 256 (batch) tile and walks the
-// hidden dimension in slabs of 32: coalesced 16-byte loads, one slab ahead, into
-// registers, parked in double-buffered LDS with an XOR swizzle, read back as MFMA
-// operands.  Workgroups are persistent over vocabulary tiles and keep their
-// per-row state across tiles, so W is streamed from HBM exactly once and only
-// gridDim.x partials per row reach the merge.
+// A workgroup (4 waves) owns a 128 (vocab) x 256 (batch) tile and walks the hidden
+// dimension in slabs of 64 (128-byte row segments: full cache lines).  Workgroups are
+// persistent over vocabulary tiles and keep their per-row state across tiles, so W is
+// streamed from HBM exactly once and only gridDim.x partials per row reach the merge.
+// Two workgroups share a CU, so one's epilogue (vector ALU) overlaps the other's
+// products (matrix cores) and loads.
 //
 // Sampling without a second logarithm: argmax_v (z_v - ln E_v), E_v = -ln u_v, is
 // argmin_v E_v / exp(z_v - m); the exponential is the one the log-sum-exp needs
@@ -197,7 +197,7 @@ typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kMfBM = 128;       // vocabulary rows per tile
 constexpr int kMfBN = 256;       // batch rows per workgroup
-constexpr int kMfBK = 32;        // hidden-dim slab
+constexpr int kMfBK = 64;        // hidden-dim slab (128 bytes of a row)
 constexpr int kMfMaxGrid = 512;  // persistent workgroups along the vocabulary (2 per CU)
 constexpr float kLn2f = 0.6931471805599453f;
 
@@ -209,8 +209,10 @@ struct LmLaneState {
   int idx;
 };
 
-// 16-byte granule g (0..3) of row `row` of a [rows][32] bf16 slab
-__device__ __forceinline__ int lm_swz(int row, int g) { return row * 4 + (g ^ ((row >> 2) & 3)); }
+// LDS position (in 16-byte granules) of granule g (0..7) of row `row` of a [rows][64]
+// bf16 slab.  Sixteen lanes that read one granule column of sixteen consecutive rows
+// touch sixteen different 4-bank groups.
+__device__ __forceinline__ int lm_swz(int row, int g) { return row * 8 + (g ^ ((row >> 1) & 7)); }
 
 __device__ __forceinline__ void lm_epilogue_block(const f32x16& acc, LmLaneState& st, int vbase,
                                                   int V, bool tail, float inv_temperature, uint32_t step_c,
@@ -253,102 +255,211 @@ __device__ __forceinline__ void lm_epilogue_block(const f32x16& acc, LmLaneState
   }
 }
 
+// ---- memory pipeline of the matrix-core kernel --------------------------------
+// Both operands reach LDS through LDS-direct loads (global_load_lds_dwordx4: each
+// lane's 16 bytes land at base + 16*lane, no registers in between), so the data in
+// flight lives in LDS rings:
+//   W       [128 rows][64 k] slabs of 16 KB, ring of kNW, issued kDW slabs ahead by
+//           waves 0-1 (HBM latency);
+//   hidden  [128 rows][64 k] units of 16 KB - the two batch halves of a slab are
+//           consumed one after the other against the same W slab - ring of 2, issued one
+//           unit ahead by waves 2-3 (L2 latency).
+// The roles are split by wave because the outstanding-load counter retires in order: a
+// wave that mixed the deep and the shallow stream would drain the deep one on every
+// unit.  The compiler cannot count LDS-direct loads per buffer (it would drain them all
+// before any LDS read), so the operand reads are inline ds_read_b128 and every wait is
+// explicit.  80 KB of LDS per workgroup: two workgroups fill a CU's 160 KB.
+constexpr int kNW = 3;                              // W ring slabs
+constexpr int kDW = kNW - 1;                        // W prefetch distance (slabs)
+constexpr int kSlab = 128 * kMfBK * 2;              // 16 KB: a W slab or a hidden unit
+constexpr int kHRing = kNW * kSlab;                 // hidden ring (2 units) starts here
+constexpr int kMfLds = kHRing + 2 * kSlab;          // 80 KB
+
+template <int OFF>
+__device__ __forceinline__ u32x4 lds_read128(uint32_t addr) {
+  u32x4 v;
+  asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(OFF) : "memory");
+  return v;
+}
+// Waits until at most N LDS reads are outstanding; the operands that must have arrived
+// are tied so that no use can be scheduled above the wait.
+template <int N>
+__device__ __forceinline__ void lds_wait(u32x4& a, u32x4& b) {
+  asm volatile("s_waitcnt lgkmcnt(%2)" : "+v"(a), "+v"(b) : "n"(N) : "memory");
+}
+__device__ __forceinline__ void lds_wait_all(u32x4 (&a)[4][2]) {
+  asm volatile("s_waitcnt lgkmcnt(0)"
+               : "+v"(a[0][0]), "+v"(a[0][1]), "+v"(a[1][0]), "+v"(a[1][1]), "+v"(a[2][0]),
+                 "+v"(a[2][1]), "+v"(a[3][0]), "+v"(a[3][1])::"memory");
+}
+
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void lmhead_mfma_kernel(
     const uint16_t* __restrict__ hidden, const uint16_t* __restrict__ weight,
     const int64_t* __restrict__ seq_id, const int32_t* __restrict__ step, uint32_t key0,
     uint32_t key1, float inv_temperature, LmPartial* __restrict__ part, int C, int H, int V,
     int n_tiles, int n_parts) {
-  __shared__ u32x4 lds_w[2][kMfBM * 4];
-  __shared__ u32x4 lds_h[2][kMfBN * 4];
-  __shared__ LmPartial s_part[2][kMfBN / 2];   // wave-row 1 hands its partials to wave-row 0
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int wm = wave >> 1, wn = wave & 1;     // vocabulary half, batch half
+  __shared__ __attribute__((aligned(1024))) char smem[kMfLds];
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm = wave >> 1, wq = wave & 1;     // vocabulary half; 64-row block of a batch half
   const int l32 = lane & 31, kb = lane >> 5;
   const int c0 = blockIdx.y * kMfBN;
+  const int nkd = H / kMfBK;                   // slabs per tile
+  const uint32_t lds0 = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(smem));
+  const uint32_t pitch = static_cast<uint32_t>(H) * 2u;
 
-  // this lane owns batch rows c0 + 128*wn + 32*nt + l32
-  uint32_t step_c[4], sid_lo[4], sid_hi[4];
-  bool c_ok[4];
-  LmLaneState st[4];
+  // operand read offsets inside a slab / unit (bytes); it / nt add 32 rows = 4096 bytes
+  uint32_t a_off[4], b_off[4];
 #pragma unroll
-  for (int nt = 0; nt < 4; ++nt) {
-    const int c = c0 + 128 * wn + 32 * nt + l32;
-    c_ok[nt] = c < C;
-    const uint64_t sid = c_ok[nt] ? static_cast<uint64_t>(seq_id[c]) : 0;
-    step_c[nt] = c_ok[nt] ? static_cast<uint32_t>(step[c]) : 0;
-    sid_lo[nt] = static_cast<uint32_t>(sid);
-    sid_hi[nt] = static_cast<uint32_t>(sid >> 32);
-    st[nt] = LmLaneState{-INFINITY, 0.0f, INFINITY, 0.0f, 0.0f, 0x7fffffff};
+  for (int k16 = 0; k16 < 4; ++k16) {
+    a_off[k16] = lm_swz(64 * wm + l32, 2 * k16 + kb) * 16;
+    b_off[k16] = lm_swz(64 * wq + l32, 2 * k16 + kb) * 16;
   }
 
-  // staging: thread t moves granules t + 256*j; granule G = (row G>>2, 16-byte chunk G&3)
-  const int g_st = tid & 3;
-  const int row_st = tid >> 2;                 // + 64*j
-  const int nk = H / kMfBK;
+  // ---- loader cursors (wave-uniform) ----
+  const int my_tiles = blockIdx.x < n_tiles ? (n_tiles - 1 - blockIdx.x) / gridDim.x + 1 : 0;
+  const int total = my_tiles * nkd;            // W slabs this workgroup consumes (hidden units: 2x)
+  const bool w_loader = wave < 2;
+  // LDS position P = 64*chunk + lane of a slab holds (row P>>3, stored granule P&7); the
+  // lane fetches the global granule that the swizzle maps there.  A loader wave moves
+  // chunks 8*(wave&1) .. +7 (rows 64*(wave&1) .. +63).
+  const int ld_row = 64 * (wave & 1) + (lane >> 3);          // + 8*j
+  // byte offset of the granule for row ld_row; for row ld_row + 8*j, (row>>1)&7 differs by
+  // 4*(j&1), i.e. the offset has bit 6 flipped for odd j
+  const uint32_t ld_g = ((lane & 7) ^ ((ld_row >> 1) & 7)) * 16;
+  int ld_n = 0;                                // W slabs (w_loader) / hidden units issued so far
+  int ld_tile = blockIdx.x, ld_kd = 0, ld_ring = 0;
+  const char* wbase = reinterpret_cast<const char*>(weight);
+  const char* hbase = reinterpret_cast<const char*>(hidden);
+  // Row offsets are recomputed at every issue (a few integer ops per 16 KB) rather than
+  // held in registers.  Rows past V re-read the last vocabulary row (masked in the
+  // epilogue); rows past C duplicate the last batch row (never used).
+  auto issue_w = [&]() __attribute__((always_inline)) {     // W slab number ld_n
+    char* dst = smem + ld_ring * kSlab + (8 * (wave & 1)) * 1024;
+    const uint32_t koff = static_cast<uint32_t>(ld_kd) * (kMfBK * 2) + ld_g;
+    const int vrow = ld_tile * kMfBM + ld_row;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const int v = min(vrow + 8 * j, V - 1);
+      __builtin_amdgcn_global_load_lds(wbase + (static_cast<uint32_t>(v) * pitch + (koff ^ ((j & 1) * 64))),
+                                       dst + j * 1024, 16, 0, 0);
+    }
+    ld_ring = ld_ring + 1 == kNW ? 0 : ld_ring + 1;
+    ++ld_n;
+    if (++ld_kd == nkd) {
+      ld_kd = 0;
+      ld_tile += gridDim.x;
+    }
+  };
+  auto issue_h = [&]() __attribute__((always_inline)) {     // hidden unit number ld_n: (slab ld_n>>1, half ld_n&1)
+    char* dst = smem + kHRing + (ld_n & 1) * kSlab + (8 * (wave & 1)) * 1024;
+    const uint32_t koff = static_cast<uint32_t>(ld_kd) * (kMfBK * 2) + ld_g;
+    const int crow = c0 + 128 * (ld_n & 1) + ld_row;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const int c = min(crow + 8 * j, C - 1);
+      __builtin_amdgcn_global_load_lds(hbase + (static_cast<uint32_t>(c) * pitch + (koff ^ ((j & 1) * 64))),
+                                       dst + j * 1024, 16, 0, 0);
+    }
+    if ((ld_n & 1) && ++ld_kd == nkd) ld_kd = 0;
+    ++ld_n;
+  };
+  if (w_loader) {
+    for (int i = 0; i < kDW && ld_n < total; ++i) issue_w();
+  } else if (total > 0) {
+    issue_h();
+  }
 
+  // this lane owns batch rows c0 + 128*half + 64*wq + 32*nt + l32 (state index 2*half + nt);
+  // their stream keys stay in registers (a global load inside the tile loop would drain
+  // the prefetch queue)
+  LmLaneState st[4];
+  uint32_t step_c[4], sid_lo[4], sid_hi[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    st[i] = LmLaneState{-INFINITY, 0.0f, INFINITY, 0.0f, 0.0f, 0x7fffffff};
+    const int c = c0 + 128 * (i >> 1) + 64 * wq + 32 * (i & 1) + l32;
+    const uint64_t sid = c < C ? static_cast<uint64_t>(seq_id[c]) : 0;
+    step_c[i] = c < C ? static_cast<uint32_t>(step[c]) : 0;
+    sid_lo[i] = static_cast<uint32_t>(sid);
+    sid_hi[i] = static_cast<uint32_t>(sid >> 32);
+  }
+
+  int d_idx = 0, ring = 0;                     // W slab being consumed (flat index), its ring slot
   for (int tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
     const int v0 = tile * kMfBM;
-    f32x16 acc[2][4];
+    f32x16 acc[2][2][2];                       // [batch half][it][nt]
 #pragma unroll
-    for (int it = 0; it < 2; ++it)
+    for (int i = 0; i < 8; ++i)
 #pragma unroll
-      for (int nt = 0; nt < 4; ++nt)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) acc[it][nt][r] = 0.0f;
+      for (int r = 0; r < 16; ++r) acc[i >> 2][(i >> 1) & 1][i & 1][r] = 0.0f;
 
-    u32x4 rw[2], rh[4];
-    auto load_regs = [&](const int ks) __attribute__((always_inline)) {
-      const size_t koff = static_cast<size_t>(ks) * kMfBK + g_st * 8;
+    for (int kd = 0; kd < nkd; ++kd, ++d_idx) {
+      // ---- top: W slab d_idx and hidden unit (d_idx, half 0) have landed ----
+      if (w_loader && d_idx + kDW <= total) {
+        asm volatile("s_waitcnt vmcnt(%0)" ::"n"(8 * (kDW - 1)) : "memory");
+      } else {
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+      }
+      asm volatile("s_barrier" ::: "memory");   // ... for every wave; all are done with slab d_idx-1
+      if (w_loader) {
+        if (ld_n < total) issue_w();
+      } else {
+        issue_h();                              // unit (d_idx, half 1): always exists
+      }
+      const uint32_t wb = lds0 + ring * kSlab;
+      ring = ring + 1 == kNW ? 0 : ring + 1;
+      u32x4 a[4][2];
 #pragma unroll
-      for (int j = 0; j < 2; ++j) {
-        const int v = v0 + row_st + 64 * j;
-        rw[j] = u32x4{0u, 0u, 0u, 0u};
-        if (v < V) rw[j] = *reinterpret_cast<const u32x4*>(weight + static_cast<size_t>(v) * H + koff);
+      for (int k16 = 0; k16 < 4; ++k16) {
+        a[k16][0] = lds_read128<0>(wb + a_off[k16]);
+        a[k16][1] = lds_read128<4096>(wb + a_off[k16]);
       }
 #pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        const int c = c0 + row_st + 64 * j;
-        rh[j] = u32x4{0u, 0u, 0u, 0u};
-        if (c < C) rh[j] = *reinterpret_cast<const u32x4*>(hidden + static_cast<size_t>(c) * H + koff);
-      }
-    };
-
-    load_regs(0);
-    for (int ks = 0; ks < nk; ++ks) {
-      const int sb = ks & 1;
+      for (int half = 0; half < 2; ++half) {
+        if (half == 1) {
+          // ---- middle: hidden unit (d_idx, half 1) has landed ----
+          if (!w_loader) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // (W loaders keep their slabs in flight)
+          asm volatile("s_barrier" ::: "memory");             // all are done with unit (d_idx, half 0)
+          if (!w_loader && ld_n < 2 * total) issue_h();       // unit (d_idx+1, half 0)
+        }
+        const uint32_t hb = lds0 + kHRing + half * kSlab;
+        u32x4 b[2][2];
+        b[0][0] = lds_read128<0>(hb + b_off[0]);
+        b[0][1] = lds_read128<4096>(hb + b_off[0]);
+        if (half == 0) lds_wait_all(a);         // (also covers b[0])
 #pragma unroll
-      for (int j = 0; j < 2; ++j) lds_w[sb][lm_swz(row_st + 64 * j, g_st)] = rw[j];
+        for (int k16 = 0; k16 < 4; ++k16) {
+          const int cur = k16 & 1, nxt = cur ^ 1;
+          if (k16 < 3) {
+            b[nxt][0] = lds_read128<0>(hb + b_off[k16 + 1]);
+            b[nxt][1] = lds_read128<4096>(hb + b_off[k16 + 1]);
+            lds_wait<2>(b[cur][0], b[cur][1]);
+          } else {
+            lds_wait<0>(b[cur][0], b[cur][1]);
+          }
+          const bf16x8 fb0 = __builtin_bit_cast(bf16x8, b[cur][0]);
+          const bf16x8 fb1 = __builtin_bit_cast(bf16x8, b[cur][1]);
 #pragma unroll
-      for (int j = 0; j < 4; ++j) lds_h[sb][lm_swz(row_st + 64 * j, g_st)] = rh[j];
-      if (ks + 1 < nk) load_regs(ks + 1);
-      __syncthreads();
-#pragma unroll
-      for (int k16 = 0; k16 < 2; ++k16) {
-        bf16x8 a[2], b[4];
-#pragma unroll
-        for (int it = 0; it < 2; ++it)
-          a[it] = __builtin_bit_cast(bf16x8, lds_w[sb][lm_swz(64 * wm + 32 * it + l32, 2 * k16 + kb)]);
-#pragma unroll
-        for (int nt = 0; nt < 4; ++nt)
-          b[nt] = __builtin_bit_cast(bf16x8, lds_h[sb][lm_swz(128 * wn + 32 * nt + l32, 2 * k16 + kb)]);
-#pragma unroll
-        for (int it = 0; it < 2; ++it)
-#pragma unroll
-          for (int nt = 0; nt < 4; ++nt)
-            acc[it][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[it], b[nt], acc[it][nt], 0, 0, 0);
+          for (int it = 0; it < 2; ++it) {
+            const bf16x8 fa = __builtin_bit_cast(bf16x8, a[k16][it]);
+            acc[half][it][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa, fb0, acc[half][it][0], 0, 0, 0);
+            acc[half][it][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa, fb1, acc[half][it][1], 0, 0, 0);
+          }
+        }
       }
     }
-    __syncthreads();   // the next tile's first slab reuses an LDS buffer
 
     const bool tail = v0 + kMfBM > V;   // only the last tile can hold rows past V
     // written out per batch block: the unrolled body is too large for the unroll pragma
-    auto epilogue = [&](auto ntc) __attribute__((always_inline)) {
-      constexpr int nt = decltype(ntc)::value;
-      if (c_ok[nt]) {
-        lm_epilogue_block(acc[0][nt], st[nt], v0 + 64 * wm + 4 * kb, V, tail, inv_temperature,
-                          step_c[nt], sid_lo[nt], sid_hi[nt], key0, key1);
-        lm_epilogue_block(acc[1][nt], st[nt], v0 + 64 * wm + 32 + 4 * kb, V, tail, inv_temperature,
-                          step_c[nt], sid_lo[nt], sid_hi[nt], key0, key1);
+    auto epilogue = [&](auto ic) __attribute__((always_inline)) {
+      constexpr int i = decltype(ic)::value;       // state index = 2*half + nt
+      const int c = c0 + 128 * (i >> 1) + 64 * wq + 32 * (i & 1) + l32;
+      if (c < C) {
+        lm_epilogue_block(acc[i >> 1][0][i & 1], st[i], v0 + 64 * wm + 4 * kb, V, tail,
+                          inv_temperature, step_c[i], sid_lo[i], sid_hi[i], key0, key1);
+        lm_epilogue_block(acc[i >> 1][1][i & 1], st[i], v0 + 64 * wm + 32 + 4 * kb, V, tail,
+                          inv_temperature, step_c[i], sid_lo[i], sid_hi[i], key0, key1);
       }
     };
     epilogue(std::integral_constant<int, 0>{});
@@ -357,16 +468,19 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     epilogue(std::integral_constant<int, 3>{});
   }
 
-  // lane state -> partial; combine the two k-halves of a wave, then the two wave-rows
+  // lane state -> partial; combine the two k-halves of a wave, then the two vocabulary
+  // halves.  The exchange buffer reuses the ring memory: all slabs have been consumed.
+  asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
+  LmPartial(*s_part)[kMfBN / 2] = reinterpret_cast<LmPartial(*)[kMfBN / 2]>(smem);
 #pragma unroll
-  for (int nt = 0; nt < 4; ++nt) {
+  for (int i = 0; i < 4; ++i) {
     LmPartial p;
-    p.m = st[nt].m;
-    p.s = st[nt].s;
-    p.z = st[nt].z_best;
-    p.idx = st[nt].idx;
+    p.m = st[i].m;
+    p.s = st[i].s;
+    p.z = st[i].z_best;
+    p.idx = st[i].idx;
     // perturbed score z + G with G = -ln(E), E = -ln u = e_best * ln 2
-    p.best = st[nt].idx == 0x7fffffff ? -INFINITY : st[nt].z_best - logf(st[nt].e_best * kLn2f);
+    p.best = st[i].idx == 0x7fffffff ? -INFINITY : st[i].z_best - logf(st[i].e_best * kLn2f);
     LmPartial o;
     o.m = __shfl_xor(p.m, 32, kWave);
     o.s = __shfl_xor(p.s, 32, kWave);
@@ -374,11 +488,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     o.z = __shfl_xor(p.z, 32, kWave);
     o.idx = __shfl_xor(p.idx, 32, kWave);
     combine(p, o);
-    if (wm == 1 && kb == 0) s_part[wn][32 * nt + l32] = p;
+    if (wm == 1 && kb == 0) s_part[wq][32 * i + l32] = p;
     __syncthreads();
     if (wm == 0 && kb == 0) {
-      combine(p, s_part[wn][32 * nt + l32]);
-      const int c = c0 + 128 * wn + 32 * nt + l32;
+      combine(p, s_part[wq][32 * i + l32]);
+      const int c = c0 + 128 * (i >> 1) + 64 * wq + 32 * (i & 1) + l32;
       if (c < C) part[static_cast<size_t>(c) * n_parts + blockIdx.x] = p;
     }
     __syncthreads();
@@ -419,7 +533,9 @@ int launch_lmhead_logprob(const void* hidden, const void* weight, const int64_t*
   const uint32_t key0 = static_cast<uint32_t>(seed), key1 = static_cast<uint32_t>(seed >> 32);
   const float inv_t = 1.0f / temperature;
   int n_parts = w.n_tiles;
-  if (dtype == 1 && H % kMfBK == 0) {
+  // the matrix-core kernel addresses W with 32-bit byte offsets
+  if (dtype == 1 && H % kMfBK == 0 && static_cast<uint64_t>(V) * H * 2 < (1ull << 32) &&
+      static_cast<uint64_t>(C) * H * 2 < (1ull << 32)) {
     const int n_tiles = (V + kMfBM - 1) / kMfBM;
     n_parts = n_tiles < kMfMaxGrid ? n_tiles : kMfMaxGrid;   // <= w.n_tiles: fits the workspace
     const dim3 grid(n_parts, (C + kMfBN - 1) / kMfBN);
