@@ -269,11 +269,13 @@ __device__ __forceinline__ void lm_epilogue_block(const f32x16& acc, LmLaneState
 // unit.  The compiler cannot count LDS-direct loads per buffer (it would drain them all
 // before any LDS read), so the operand reads are inline ds_read_b128 and every wait is
 // explicit.  80 KB of LDS per workgroup: two workgroups fill a CU's 160 KB.
-constexpr int kNW = 3;                              // W ring slabs
+constexpr int kNW = 2;                              // W ring slabs
 constexpr int kDW = kNW - 1;                        // W prefetch distance (slabs)
+constexpr int kNH = 3;                              // hidden ring units
+constexpr int kDH = kNH - 1;                        // hidden prefetch distance (units)
 constexpr int kSlab = 128 * kMfBK * 2;              // 16 KB: a W slab or a hidden unit
-constexpr int kHRing = kNW * kSlab;                 // hidden ring (2 units) starts here
-constexpr int kMfLds = kHRing + 2 * kSlab;          // 80 KB
+constexpr int kHRing = kNW * kSlab;                 // hidden ring starts here
+constexpr int kMfLds = kHRing + kNH * kSlab;        // 80 KB
 
 template <int OFF>
 __device__ __forceinline__ u32x4 lds_read128(uint32_t addr) {
@@ -328,7 +330,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   // 4*(j&1), i.e. the offset has bit 6 flipped for odd j
   const uint32_t ld_g = ((lane & 7) ^ ((ld_row >> 1) & 7)) * 16;
   int ld_n = 0;                                // W slabs (w_loader) / hidden units issued so far
-  int ld_tile = blockIdx.x, ld_kd = 0, ld_ring = 0;
+  int ld_tile = blockIdx.x, ld_kd = 0, ld_ring = 0, h_ring = 0;
   const char* wbase = reinterpret_cast<const char*>(weight);
   const char* hbase = reinterpret_cast<const char*>(hidden);
   // Row offsets are recomputed at every issue (a few integer ops per 16 KB) rather than
@@ -352,7 +354,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     }
   };
   auto issue_h = [&]() __attribute__((always_inline)) {     // hidden unit number ld_n: (slab ld_n>>1, half ld_n&1)
-    char* dst = smem + kHRing + (ld_n & 1) * kSlab + (8 * (wave & 1)) * 1024;
+    char* dst = smem + kHRing + h_ring * kSlab + (8 * (wave & 1)) * 1024;
+    h_ring = h_ring + 1 == kNH ? 0 : h_ring + 1;
     const uint32_t koff = static_cast<uint32_t>(ld_kd) * (kMfBK * 2) + ld_g;
     const int crow = c0 + 128 * (ld_n & 1) + ld_row;
 #pragma unroll
@@ -366,8 +369,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   };
   if (w_loader) {
     for (int i = 0; i < kDW && ld_n < total; ++i) issue_w();
-  } else if (total > 0) {
-    issue_h();
+  } else {
+    for (int i = 0; i < kDH && ld_n < 2 * total; ++i) issue_h();
   }
 
   // this lane owns batch rows c0 + 128*half + 64*wq + 32*nt + l32 (state index 2*half + nt);
@@ -385,7 +388,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     sid_hi[i] = static_cast<uint32_t>(sid >> 32);
   }
 
-  int d_idx = 0, ring = 0;                     // W slab being consumed (flat index), its ring slot
+  int d_idx = 0, ring = 0, hring = 0;          // W slab being consumed (flat index), W / hidden ring slots
   for (int tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
     const int v0 = tile * kMfBM;
     f32x16 acc[2][2][2];                       // [batch half][it][nt]
@@ -398,6 +401,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
       // ---- top: W slab d_idx and hidden unit (d_idx, half 0) have landed ----
       if (w_loader && d_idx + kDW <= total) {
         asm volatile("s_waitcnt vmcnt(%0)" ::"n"(8 * (kDW - 1)) : "memory");
+      } else if (!w_loader && 2 * d_idx + kDH <= 2 * total) {
+        asm volatile("s_waitcnt vmcnt(%0)" ::"n"(8 * (kDH - 1)) : "memory");
       } else {
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
       }
@@ -405,7 +410,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
       if (w_loader) {
         if (ld_n < total) issue_w();
       } else {
-        issue_h();                              // unit (d_idx, half 1): always exists
+        if (ld_n < 2 * total) issue_h();        // refills the slot of unit (d_idx-1, half 1)
       }
       const uint32_t wb = lds0 + ring * kSlab;
       ring = ring + 1 == kNW ? 0 : ring + 1;
@@ -419,11 +424,18 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
       for (int half = 0; half < 2; ++half) {
         if (half == 1) {
           // ---- middle: hidden unit (d_idx, half 1) has landed ----
-          if (!w_loader) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // (W loaders keep their slabs in flight)
+          if (!w_loader) {                                    // (W loaders keep their slabs in flight)
+            if (2 * d_idx + 1 + kDH <= 2 * total) {
+              asm volatile("s_waitcnt vmcnt(%0)" ::"n"(8 * (kDH - 1)) : "memory");
+            } else {
+              asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            }
+          }
           asm volatile("s_barrier" ::: "memory");             // all are done with unit (d_idx, half 0)
-          if (!w_loader && ld_n < 2 * total) issue_h();       // unit (d_idx+1, half 0)
+          if (!w_loader && ld_n < 2 * total) issue_h();       // refills that unit's slot
         }
-        const uint32_t hb = lds0 + kHRing + half * kSlab;
+        const uint32_t hb = lds0 + kHRing + hring * kSlab;
+        hring = hring + 1 == kNH ? 0 : hring + 1;
         u32x4 b[2][2];
         b[0][0] = lds_read128<0>(hb + b_off[0]);
         b[0][1] = lds_read128<4096>(hb + b_off[0]);
