@@ -24,12 +24,13 @@ constexpr int kErrLaunch = -4;   // COPRIS_ELAUNCH
 // ---- decode attention -------------------------------------------------------
 constexpr int kAttnChunkTokens = 512;   // split-K granularity along the context
 constexpr int kAttnMaxGroup = 16;       // query heads per kv head, at most
+constexpr int kAttnWaves = 256 * 8;     // persistent wavefronts of the tuned split kernel (8 per CU)
 
 // Workspace carve-up (byte offsets from a 256-byte aligned base).
 struct AttnWorkspace {
   size_t hdr;       // int32[64]:  [0] number of (seq, chunk) entries, [1] work counter
-  size_t seq_off;   // int32[C+1]: first list entry of every sequence
-  size_t list;      // int2[max_list]: (seq, chunk)
+  size_t seq_off;   // int32[C+1]: first list entry (generic path) / page prefix (tuned path) of every sequence
+  size_t list;      // int2[]: (seq, chunk) items (generic path) / flat slot entries (tuned path)
   size_t ml;        // float2[max_list*Hkv*g]: running max (log2 domain) and sum of weights
   size_t acc;       // float[max_list*Hkv*g*D]: un-normalised weighted value sums
   size_t total;

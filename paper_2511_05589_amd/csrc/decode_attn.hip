@@ -1,25 +1,36 @@
 // Paged-KV grouped-query decode attention for gfx950, split along the context.
 //
-//   worklist kernel   ctx_len -> compact list of (sequence, 512-token chunk) entries
-//   split kernel      one wavefront per (entry, kv head): online-softmax partial
-//                     (running max, weight sum, weighted value sum) for the g query
-//                     heads that share the kv head
-//   merge kernel      per (sequence, kv head): log-sum-exp combination of the
-//                     partials in chunk order, normalisation, store
+// Tuned path (bf16, head_dim 128, page 16): the (kv head, page) slabs of the whole pool
+// are laid out as ONE flat sequence of "slots" (sequence-major, then kv head, then page)
+// and cut into equal contiguous shares, one per persistent wavefront ("stream-K"): the
+// split is balanced to one page whatever the length distribution, a 32k-token resumed
+// trajectory is simply spread over many wavefronts, and nothing is scheduled at run time.
+//   scan kernel    ctx_len -> page prefix sums, slots per wavefront
+//   fill kernel    block table -> flat slot list (physical page, kv head, sequence,
+//                  tokens valid in the page)
+//   split kernel   one wavefront per share: walks its slots with a three-page-deep
+//                  register prefetch; whenever the (sequence, kv head) changes it writes
+//                  the online-softmax partial (running max, weight sum, weighted value
+//                  sum) of the g query heads that share the kv head
+//   merge kernel   per (sequence, query head): log-sum-exp combination of the partials
+//                  in share order, normalisation, store
+// The partition depends on ctx_len only, the merge order is fixed: results are bitwise
+// reproducible and do not depend on the physical page order.
 //
-// The bf16 split kernel (head_dim 128, page 16) keeps the kernel HBM-bound by doing
-// both contractions on the matrix cores with the TOKENS (scores) or the head
-// dimension (values) as the 16-row M side and the 16-padded group of query heads as
-// the N side:
+// The split kernel keeps the kernel HBM-bound by doing both contractions on the matrix
+// cores with the TOKENS (scores) or the head dimension (values) as the 16-row M side and
+// the 16-padded group of query heads as the N side:
 //     S^T[token][head] = K_page[token][:] . Q[head][:]          4 x mfma 16x16x32
 //     O^T[d][head]    += V_page^T[d][token] . P^T[token][head]  8 x mfma 16x16x16
-// With that orientation the score tile leaves the first product already in the
-// register layout the second one wants for P^T, and every per-head softmax quantity
-// (max, sum, rescale factor) lives in the lane that owns the head.
-// A (page, kv head) slab is one contiguous 4 KB run: it is fetched with fully
-// coalesced 16-byte loads several pages ahead into registers, parked in LDS with an
-// XOR swizzle, and read back in MFMA operand layout (V through the transposing LDS
-// read).  The physical page order never changes the arithmetic order.
+// With that orientation the score tile leaves the first product already in the register
+// layout the second one wants for P^T, and every per-head softmax quantity (max, sum,
+// rescale factor) lives in the lane that owns the head.  A (page, kv head) slab is one
+// contiguous 4 KB run: it is fetched with fully coalesced 16-byte loads, parked in LDS
+// with an XOR swizzle, and read back in MFMA operand layout (V through the transposing
+// LDS read).
+//
+// Generic path (fp32, other head_dim / page sizes): a list of (sequence, 512-token chunk)
+// items, one workgroup per (item, kv head) on the vector ALU, same partial format.
 #include <type_traits>
 
 #include "copris_device.h"
@@ -46,12 +57,19 @@ AttnWorkspace attn_workspace_layout(int C, int Hq, int Hkv, int D, int page_size
   const int64_t max_tokens = static_cast<int64_t>(max_pages) * page_size;
   const int64_t chunks = (max_tokens + kAttnChunkTokens - 1) / kAttnChunkTokens;
   w.max_list = static_cast<int64_t>(C) * (chunks > 0 ? chunks : 1);
+  // list: (seq, chunk) items of the generic path, or the flat slot list of the tuned path
+  const int64_t max_slots = static_cast<int64_t>(C) * max_pages * Hkv;
+  const int64_t list_len = w.max_list > max_slots ? w.max_list : max_slots;
+  // partials: one per (item, kv head), or one per (wavefront, segment) overlap
+  const int64_t part_a = w.max_list * Hkv;
+  const int64_t part_b = static_cast<int64_t>(kAttnWaves) + static_cast<int64_t>(C) * Hkv;
+  const int64_t parts = part_a > part_b ? part_a : part_b;
   size_t off = 0;
   w.hdr = off;      off = align256(off + 64 * sizeof(int32_t));
   w.seq_off = off;  off = align256(off + (static_cast<size_t>(C) + 1) * sizeof(int32_t));
-  w.list = off;     off = align256(off + static_cast<size_t>(w.max_list) * sizeof(int2));
-  w.ml = off;       off = align256(off + static_cast<size_t>(w.max_list) * Hkv * g * sizeof(float2));
-  w.acc = off;      off = align256(off + static_cast<size_t>(w.max_list) * Hkv * g * D * sizeof(float));
+  w.list = off;     off = align256(off + static_cast<size_t>(list_len) * sizeof(int2));
+  w.ml = off;       off = align256(off + static_cast<size_t>(parts) * g * sizeof(float2));
+  w.acc = off;      off = align256(off + static_cast<size_t>(parts) * g * D * sizeof(float));
   w.total = off;
   return w;
 }
@@ -241,12 +259,67 @@ __global__ __launch_bounds__(256) void attn_split_generic_kernel(
 }
 
 // --------------------------------------------------------------------------
-// a2 (tuned): bf16, head_dim 128, page 16, g <= 16.  One wavefront per workgroup;
-// wavefronts pull (entry, kv head) items from a counter until the list is empty.
+// a1/a2 (tuned): bf16, head_dim 128, page 16, g <= 16, flat slot stream.
 // --------------------------------------------------------------------------
 constexpr int kD = 128;
 constexpr int kP = 16;
 constexpr int kPageGranules = kP * kD * 2 / 16;   // 256 16-byte granules per (page, kv head)
+
+// hdr[0] = slots in total, hdr[1] = slots per wavefront.  seq_pg[i] = pages of sequences < i.
+__global__ __launch_bounds__(kListThreads) void attn_scan_kernel(
+    const int32_t* __restrict__ ctx_len, int C, int max_tokens, int Hkv, int32_t* __restrict__ hdr,
+    int32_t* __restrict__ seq_pg) {
+  __shared__ int s_wave[kListThreads / kWave];
+  __shared__ int s_carry;
+  const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
+  if (tid == 0) s_carry = 0;
+  __syncthreads();
+  for (int base = 0; base < C; base += kListThreads) {
+    const int i = base + tid;
+    int n = i < C ? ctx_len[i] : 0;
+    n = n < 0 ? 0 : (n > max_tokens ? max_tokens : n);
+    const int npg = (n + kP - 1) / kP;
+    int incl = npg;
+#pragma unroll
+    for (int o = 1; o < kWave; o <<= 1) {
+      const int up = __shfl_up(incl, o, kWave);
+      if (lane >= o) incl += up;
+    }
+    if (lane == kWave - 1) s_wave[wave] = incl;
+    __syncthreads();
+    int before = s_carry;
+    for (int w = 0; w < wave; ++w) before += s_wave[w];
+    if (i < C) seq_pg[i] = before + incl - npg;
+    __syncthreads();
+    if (tid == kListThreads - 1) s_carry = before + incl;
+    __syncthreads();
+  }
+  if (tid == 0) {
+    const int total = s_carry * Hkv;
+    seq_pg[C] = s_carry;
+    hdr[0] = total;
+    hdr[1] = total > 0 ? (total + kAttnWaves - 1) / kAttnWaves : 1;
+  }
+}
+
+// Slot entry: x = physical page, y = (tokens valid in the page - 1) | kv head << 4 | sequence << 12.
+__global__ __launch_bounds__(256) void attn_fill_kernel(const int32_t* __restrict__ block_table,
+                                                        const int32_t* __restrict__ ctx_len,
+                                                        const int32_t* __restrict__ seq_pg,
+                                                        int2* __restrict__ entries, int Hkv,
+                                                        int max_pages, int max_tokens) {
+  const int seq = blockIdx.x;
+  int n = ctx_len[seq];
+  n = n < 0 ? 0 : (n > max_tokens ? max_tokens : n);
+  const int npg = (n + kP - 1) / kP;
+  const size_t base = static_cast<size_t>(seq_pg[seq]) * Hkv;
+  const int32_t* bt = block_table + static_cast<size_t>(seq) * max_pages;
+  for (int e = threadIdx.x; e < npg * Hkv; e += 256) {
+    const int kvh = e / npg, p = e - kvh * npg;
+    const int valid = min(kP, n - p * kP);
+    entries[base + e] = make_int2(bt[p], (valid - 1) | (kvh << 4) | (seq << 12));
+  }
+}
 
 __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
   uint32_t r;
@@ -273,155 +346,185 @@ __device__ __forceinline__ void load_page(PageRegs& r, const u32x4* __restrict__
 __device__ __forceinline__ int swz_k(int row, int c) { return row * 16 + (c ^ (row & 15)); }
 __device__ __forceinline__ int swz_v(int row, int c) { return row * 16 + (c ^ ((row & 7) << 1)); }
 
+// s_waitcnt vmcnt(0) with the other counters left alone (gfx9 encoding)
+#define COPRIS_WAIT_VM0() __builtin_amdgcn_s_waitcnt(0x0F70)
+
 template <int NS>
-__global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2))) void attn_split_mfma_kernel(
+__global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2))) void attn_split_flat_kernel(
     const uint16_t* __restrict__ q, const u32x4* __restrict__ k_cache,
-    const u32x4* __restrict__ v_cache, const int32_t* __restrict__ block_table,
-    const int32_t* __restrict__ ctx_len, int32_t* __restrict__ hdr, const int2* __restrict__ list,
-    float2* __restrict__ ws_ml, float* __restrict__ ws_acc, int Hq, int Hkv, int g, int max_pages,
-    int max_tokens, float scale_log2e) {
+    const u32x4* __restrict__ v_cache, const int32_t* __restrict__ hdr,
+    const int2* __restrict__ entries, float2* __restrict__ ws_ml, float* __restrict__ ws_acc,
+    int Hq, int Hkv, int g, float scale_log2e) {
   __shared__ u32x4 lds_k[kPageGranules];
   __shared__ u32x4 lds_v[kPageGranules];
   const int lane = threadIdx.x;
   const int head = lane & 15;     // N index of both products: the query head of the group
   const int b = lane >> 4;        // k-group of the MFMA operand layouts
-  const int n_items = hdr[0] * Hkv;
+  const int total = hdr[0], share = hdr[1];
+  const int wv = blockIdx.x;
+  const int64_t first = static_cast<int64_t>(wv) * share;
+  if (first >= total) return;
+  const int n = static_cast<int>(min(static_cast<int64_t>(share), total - first));   // slots of this wavefront
+  const int2* __restrict__ ent = entries + first;
 
-  while (true) {
-    int item = 0;
-    if (lane == 0) item = atomicAdd(&hdr[1], 1);
-    item = __builtin_amdgcn_readfirstlane(item);
-    if (item >= n_items) break;
-    const int li = item / Hkv, kvh = item - li * Hkv;
-    const int seq = list[li].x, chunk = list[li].y;
-    int n = ctx_len[seq];
-    n = n > max_tokens ? max_tokens : n;
-    const int t0 = chunk * kAttnChunkTokens;
-    const int t1 = min(n, t0 + kAttnChunkTokens);
-    const int npg = (t1 - t0 + kP - 1) / kP;          // 1..32 pages
-    const int my_page =
-        lane < npg ? block_table[static_cast<size_t>(seq) * max_pages + t0 / kP + lane] : 0;
+  // state of the segment (sequence, kv head) being accumulated
+  int cur_seg = -1;
+  bf16x8 qf[4];
+  float m_run = -INFINITY, l_run = 0.0f;
+  f32x4 o[8];
 
-    // Q^T operand: lane (head, b) holds Q[head][32*kk + 8*b .. +8]; padded heads are zero
-    bf16x8 qf[4];
-    {
-      const u32x4* qrow =
-          reinterpret_cast<const u32x4*>(q + (static_cast<size_t>(seq) * Hq + kvh * g + head) * kD);
-#pragma unroll
-      for (int kk = 0; kk < 4; ++kk) {
-        u32x4 x = {0u, 0u, 0u, 0u};
-        if (head < g) x = qrow[kk * 4 + b];
-        qf[kk] = __builtin_bit_cast(bf16x8, x);
-      }
-    }
-
-    float m_run = -INFINITY, l_run = 0.0f;
-    f32x4 o[8];
-#pragma unroll
-    for (int dt = 0; dt < 8; ++dt) o[dt] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
-
-    // One page: park it in LDS, refill its registers with the page NS ahead, then
-    // both products.  `pp` is the page's index inside the chunk (wave-uniform).
-    // `steady`: the page NS ahead exists and this page is full, so the refill is
-    // unconditional (which lets the compiler count outstanding loads exactly and keep
-    // the younger stages in flight) and no masking is needed.
-    auto do_page = [&](PageRegs& r, const int pp, auto steady) __attribute__((always_inline)) {
-      constexpr bool kSteady = decltype(steady)::value;
-      // granule (i*64+lane) = token row 4i+b, column granule `head`
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        lds_k[swz_k(4 * i + b, head)] = r.k[i];
-        lds_v[swz_v(4 * i + b, head)] = r.v[i];
-      }
-      if (kSteady || pp + NS < npg)
-        load_page(r, k_cache, v_cache, __builtin_amdgcn_readlane(my_page, pp + NS), Hkv, kvh, lane);
-      __syncthreads();
-
-      // S^T[token][head]: A = K rows (token = lane&15), B = Q^T
-      f32x4 sc = {0.0f, 0.0f, 0.0f, 0.0f};
-#pragma unroll
-      for (int kk = 0; kk < 4; ++kk) {
-        const bf16x8 kf = __builtin_bit_cast(bf16x8, lds_k[swz_k(head, 4 * kk + b)]);
-        sc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf, qf[kk], sc, 0, 0, 0);
-      }
-      // this lane: head `head`, tokens 4b..4b+3 of the page
-      const int valid = t1 - t0 - pp * kP;   // tokens of this page inside the context
-      float t[4];
-#pragma unroll
-      for (int rr = 0; rr < 4; ++rr) t[rr] = sc[rr] * scale_log2e;
-      if (!kSteady && valid < kP) {
-#pragma unroll
-        for (int rr = 0; rr < 4; ++rr) t[rr] = (4 * b + rr < valid) ? t[rr] : -INFINITY;
-      }
-      float mx = fmaxf(fmaxf(t[0], t[1]), fmaxf(t[2], t[3]));
-      mx = fmaxf(mx, __shfl_xor(mx, 16, kWave));
-      mx = fmaxf(mx, __shfl_xor(mx, 32, kWave));
-      const float m_new = fmaxf(m_run, mx);
-      const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
-      m_run = m_new;
-      float p[4];
-#pragma unroll
-      for (int rr = 0; rr < 4; ++rr) p[rr] = __builtin_amdgcn_exp2f(t[rr] - m_new);
-      l_run = l_run * alpha + ((p[0] + p[1]) + (p[2] + p[3]));
-      const uint2 pk = make_uint2(pack_bf16x2(p[0], p[1]), pack_bf16x2(p[2], p[3]));
-      const s16x4 pf = __builtin_bit_cast(s16x4, pk);
-      if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {
-#pragma unroll
-        for (int dt = 0; dt < 8; ++dt) o[dt] *= alpha;
-      }
-      // O^T[d][head] += V^T[d][token] P^T[token][head]: A = V^T via the transposing
-      // read (lane supplies row 4b + L/4, columns 16dt + 4(L%4)..+3, L = lane&15)
-      const int vrow = 4 * b + (head >> 2);
-      const char* vbase = reinterpret_cast<const char*>(lds_v) + (head & 1) * 8;
-#pragma unroll
-      for (int dt = 0; dt < 8; ++dt) {
-        const char* addr = vbase + swz_v(vrow, 2 * dt + ((head & 3) >> 1)) * 16;
-        s16x4 vf = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-            (__attribute__((address_space(3))) s16x4*)(addr));
-        if (!kSteady && valid < kP) {   // rows past the context may hold anything (NaN): zero them
-#pragma unroll
-          for (int rr = 0; rr < 4; ++rr)
-            vf[rr] = (4 * b + rr < valid) ? vf[rr] : static_cast<short>(0);
-        }
-        o[dt] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(vf, pf, o[dt], 0, 0, 0);
-      }
-      __syncthreads();   // the next page may overwrite the LDS tiles
-    };
-
-    static_assert(NS == 3, "the page pipeline below is written out for three stages");
-    PageRegs st0, st1, st2;
-    int p0 = 0;
-    load_page(st0, k_cache, v_cache, __builtin_amdgcn_readlane(my_page, 0), Hkv, kvh, lane);
-    if (npg >= 2 * NS) {
-      load_page(st1, k_cache, v_cache, __builtin_amdgcn_readlane(my_page, 1), Hkv, kvh, lane);
-      load_page(st2, k_cache, v_cache, __builtin_amdgcn_readlane(my_page, 2), Hkv, kvh, lane);
-      do {   // steady state: every refill exists, every page is full
-        do_page(st0, p0, std::true_type{});
-        do_page(st1, p0 + 1, std::true_type{});
-        do_page(st2, p0 + 2, std::true_type{});
-        p0 += NS;
-      } while (p0 + 2 * NS <= npg);
-    } else {
-      if (1 < npg) load_page(st1, k_cache, v_cache, __builtin_amdgcn_readlane(my_page, 1), Hkv, kvh, lane);
-      if (2 < npg) load_page(st2, k_cache, v_cache, __builtin_amdgcn_readlane(my_page, 2), Hkv, kvh, lane);
-    }
-    for (; p0 < npg; p0 += NS) {   // the last 3..5 pages of the chunk (or a short chunk)
-      do_page(st0, p0, std::false_type{});
-      if (p0 + 1 < npg) do_page(st1, p0 + 1, std::false_type{});
-      if (p0 + 2 < npg) do_page(st2, p0 + 2, std::false_type{});
-    }
-
-    // partial results of this item: lane (head, b) owns d = 16dt + 4b + r
-    l_run += __shfl_xor(l_run, 16, kWave);
-    l_run += __shfl_xor(l_run, 32, kWave);
+  auto flush = [&]() __attribute__((always_inline)) {   // partial of (this wavefront, cur_seg)
+    float l_all = l_run;
+    l_all += __shfl_xor(l_all, 16, kWave);
+    l_all += __shfl_xor(l_all, 32, kWave);
     if (head < g) {
-      float* dst = ws_acc + (static_cast<size_t>(item) * g + head) * kD + 4 * b;
+      const size_t slot = (static_cast<size_t>(wv) + cur_seg) * g + head;
+      float* dst = ws_acc + slot * kD + 4 * b;    // lane (head, b) owns d = 16dt + 4b + r
 #pragma unroll
       for (int dt = 0; dt < 8; ++dt)
         *reinterpret_cast<float4*>(dst + 16 * dt) = make_float4(o[dt][0], o[dt][1], o[dt][2], o[dt][3]);
-      if (b == 0) ws_ml[static_cast<size_t>(item) * g + head] = make_float2(m_run, l_run);
+      if (b == 0) ws_ml[slot] = make_float2(m_run, l_all);
+    }
+  };
+  auto begin_segment = [&](const int seq, const int kvh) __attribute__((always_inline)) {
+    cur_seg = seq * Hkv + kvh;
+    // Q^T operand: lane (head, b) holds Q[head][32*kk + 8*b .. +8]; padded heads are zero
+    const u32x4* qrow =
+        reinterpret_cast<const u32x4*>(q + (static_cast<size_t>(seq) * Hq + kvh * g + head) * kD);
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) {
+      u32x4 x = {0u, 0u, 0u, 0u};
+      if (head < g) x = qrow[kk * 4 + b];
+      qf[kk] = __builtin_bit_cast(bf16x8, x);
+    }
+    // complete these loads here (rare path) so that the common path never has to wait
+    // for anything younger than its own page prefetches
+    COPRIS_WAIT_VM0();
+    m_run = -INFINITY;
+    l_run = 0.0f;
+#pragma unroll
+    for (int dt = 0; dt < 8; ++dt) o[dt] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+  };
+
+  // One slot: park its page in LDS, refill the registers with the page NS slots ahead,
+  // then both products.  `code` is the slot's entry word (wave-uniform).
+  // steady: the slot NS ahead exists, so the refill is unconditional (which lets the
+  // compiler count outstanding loads exactly and keep the younger stages in flight).
+  auto do_slot = [&](PageRegs& r, int& code, const int i, auto steady) __attribute__((always_inline)) {
+    constexpr bool kSteady = decltype(steady)::value;
+    const int valid = (code & 15) + 1;           // tokens of this page inside the context
+    const int kvh = (code >> 4) & 255, seq = code >> 12;
+    if (seq * Hkv + kvh != cur_seg) {
+      if (cur_seg >= 0) flush();
+      begin_segment(seq, kvh);
+    }
+    // granule (j*64+lane) = token row 4j+b, column granule `head`
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      lds_k[swz_k(4 * j + b, head)] = r.k[j];
+      lds_v[swz_v(4 * j + b, head)] = r.v[j];
+    }
+    if (kSteady || i + NS < n) {
+      const int2 e = ent[i + NS];
+      code = e.y;
+      load_page(r, k_cache, v_cache, e.x, Hkv, (e.y >> 4) & 255, lane);
+    }
+    __syncthreads();
+
+    // S^T[token][head]: A = K rows (token = lane&15), B = Q^T
+    f32x4 sc = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) {
+      const bf16x8 kf = __builtin_bit_cast(bf16x8, lds_k[swz_k(head, 4 * kk + b)]);
+      sc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf, qf[kk], sc, 0, 0, 0);
+    }
+    // this lane: head `head`, tokens 4b..4b+3 of the page
+    float t[4];
+#pragma unroll
+    for (int rr = 0; rr < 4; ++rr) t[rr] = sc[rr] * scale_log2e;
+    if (valid < kP) {
+#pragma unroll
+      for (int rr = 0; rr < 4; ++rr) t[rr] = (4 * b + rr < valid) ? t[rr] : -INFINITY;
+    }
+    float mx = fmaxf(fmaxf(t[0], t[1]), fmaxf(t[2], t[3]));
+    mx = fmaxf(mx, __shfl_xor(mx, 16, kWave));
+    mx = fmaxf(mx, __shfl_xor(mx, 32, kWave));
+    const float m_new = fmaxf(m_run, mx);
+    const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+    m_run = m_new;
+    float p[4];
+#pragma unroll
+    for (int rr = 0; rr < 4; ++rr) p[rr] = __builtin_amdgcn_exp2f(t[rr] - m_new);
+    l_run = l_run * alpha + ((p[0] + p[1]) + (p[2] + p[3]));
+    const uint2 pk = make_uint2(pack_bf16x2(p[0], p[1]), pack_bf16x2(p[2], p[3]));
+    const s16x4 pf = __builtin_bit_cast(s16x4, pk);
+    if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {
+#pragma unroll
+      for (int dt = 0; dt < 8; ++dt) o[dt] *= alpha;
+    }
+    // O^T[d][head] += V^T[d][token] P^T[token][head]: A = V^T via the transposing
+    // read (lane supplies row 4b + L/4, columns 16dt + 4(L%4)..+3, L = lane&15)
+    const int vrow = 4 * b + (head >> 2);
+    const char* vbase = reinterpret_cast<const char*>(lds_v) + (head & 1) * 8;
+#pragma unroll
+    for (int dt = 0; dt < 8; ++dt) {
+      const char* addr = vbase + swz_v(vrow, 2 * dt + ((head & 3) >> 1)) * 16;
+      s16x4 vf = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+          (__attribute__((address_space(3))) s16x4*)(addr));
+      if (valid < kP) {   // rows past the context may hold anything (NaN): zero them
+#pragma unroll
+        for (int rr = 0; rr < 4; ++rr)
+          vf[rr] = (4 * b + rr < valid) ? vf[rr] : static_cast<short>(0);
+      }
+      o[dt] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(vf, pf, o[dt], 0, 0, 0);
+    }
+    __syncthreads();   // the next page may overwrite the LDS tiles
+  };
+
+  static_assert(NS == 3, "the page pipeline below is written out for three stages");
+  PageRegs st0, st1, st2;
+  int c0 = 0, c1 = 0, c2 = 0;   // entry words of the slots held in st0..st2
+  int i = 0;
+  {
+    const int2 e = ent[0];
+    c0 = e.y;
+    load_page(st0, k_cache, v_cache, e.x, Hkv, (e.y >> 4) & 255, lane);
+  }
+  if (n >= 2 * NS) {
+    {
+      const int2 e = ent[1];
+      c1 = e.y;
+      load_page(st1, k_cache, v_cache, e.x, Hkv, (e.y >> 4) & 255, lane);
+    }
+    {
+      const int2 e = ent[2];
+      c2 = e.y;
+      load_page(st2, k_cache, v_cache, e.x, Hkv, (e.y >> 4) & 255, lane);
+    }
+    do {   // steady state: every refill exists
+      do_slot(st0, c0, i, std::true_type{});
+      do_slot(st1, c1, i + 1, std::true_type{});
+      do_slot(st2, c2, i + 2, std::true_type{});
+      i += NS;
+    } while (i + 2 * NS <= n);
+  } else {
+    if (1 < n) {
+      const int2 e = ent[1];
+      c1 = e.y;
+      load_page(st1, k_cache, v_cache, e.x, Hkv, (e.y >> 4) & 255, lane);
+    }
+    if (2 < n) {
+      const int2 e = ent[2];
+      c2 = e.y;
+      load_page(st2, k_cache, v_cache, e.x, Hkv, (e.y >> 4) & 255, lane);
     }
   }
+  for (; i < n; i += NS) {   // the last 3..5 slots of the share (or a short share)
+    do_slot(st0, c0, i, std::false_type{});
+    if (i + 1 < n) do_slot(st1, c1, i + 1, std::false_type{});
+    if (i + 2 < n) do_slot(st2, c2, i + 2, std::false_type{});
+  }
+  flush();
 }
 
 // --------------------------------------------------------------------------
@@ -476,6 +579,40 @@ __global__ void attn_merge_kernel(const int32_t* __restrict__ seq_off,
     lse[oh] = n > 0 ? (m_star + __builtin_amdgcn_logf(denom)) * kLn2 : -INFINITY;
 }
 
+// Merge for the flat slot stream: segment (seq, kv head) occupies slots [a, a+npg) and was
+// touched by the wavefronts a/share .. (a+npg-1)/share; the partial of (wavefront w,
+// segment s) sits at index w + s.
+template <typename T>
+__global__ void attn_merge_flat_kernel(const int32_t* __restrict__ hdr,
+                                       const int32_t* __restrict__ seq_pg,
+                                       const float2* __restrict__ ws_ml,
+                                       const float* __restrict__ ws_acc, T* __restrict__ out,
+                                       float* __restrict__ lse, int Hq, int Hkv, int g, int D) {
+  const int seq = blockIdx.x, hq = blockIdx.y, d = threadIdx.x;
+  const int kvh = hq / g, h = hq - kvh * g;
+  const int share = hdr[1];
+  const int npg = seq_pg[seq + 1] - seq_pg[seq];
+  const int64_t a = static_cast<int64_t>(seq_pg[seq]) * Hkv + static_cast<int64_t>(kvh) * npg;
+  const int seg = seq * Hkv + kvh;
+  const int w0 = npg > 0 ? static_cast<int>(a / share) : 0;
+  const int n = npg > 0 ? static_cast<int>((a + npg - 1) / share) - w0 + 1 : 0;
+  const size_t slot0 = (static_cast<size_t>(w0) + seg) * g + h;   // consecutive wavefronts: stride g
+  float m_star = -INFINITY;
+  for (int e = 0; e < n; ++e) m_star = fmaxf(m_star, ws_ml[slot0 + static_cast<size_t>(e) * g].x);
+  float denom = 0.0f, num = 0.0f;
+  for (int e = 0; e < n; ++e) {
+    const size_t slot = slot0 + static_cast<size_t>(e) * g;
+    const float2 ml = ws_ml[slot];
+    const float w = __builtin_amdgcn_exp2f(ml.x - m_star);
+    denom = fmaf(w, ml.y, denom);
+    num = fmaf(w, ws_acc[slot * D + d], num);
+  }
+  const size_t oh = static_cast<size_t>(seq) * Hq + hq;
+  store_out<T>(out + oh * D + d, n > 0 ? num / denom : 0.0f);
+  if (lse != nullptr && d == 0)
+    lse[oh] = n > 0 ? (m_star + __builtin_amdgcn_logf(denom)) * kLn2 : -INFINITY;
+}
+
 // --------------------------------------------------------------------------
 // host launcher
 // --------------------------------------------------------------------------
@@ -495,25 +632,37 @@ int launch_decode_attn(const void* q, const void* k_cache, const void* v_cache,
   const int max_tokens = static_cast<int>(max_tokens64);
   const float scale_log2e = scale * kLog2e;
 
+  // the flat slot stream packs the kv head in 8 bits and the sequence in 19
+  const bool tuned = dtype == 1 && D == kD && page_size == kP && Hkv <= 256 && C < (1 << 19) &&
+                     static_cast<int64_t>(C) * max_pages * Hkv < (1ll << 31);
+  if (tuned) {
+    COPRIS_PRE("attn_scan_kernel");
+    hipLaunchKernelGGL(attn_scan_kernel, dim3(1), dim3(kListThreads), 0, stream, ctx_len, C,
+                       max_tokens, Hkv, hdr, seq_off);
+    COPRIS_POST("attn_scan_kernel");
+    COPRIS_PRE("attn_fill_kernel");
+    hipLaunchKernelGGL(attn_fill_kernel, dim3(C), dim3(256), 0, stream, block_table, ctx_len,
+                       seq_off, list, Hkv, max_pages, max_tokens);
+    COPRIS_POST("attn_fill_kernel");
+    COPRIS_PRE("attn_split_flat_kernel");
+    hipLaunchKernelGGL(attn_split_flat_kernel<3>, dim3(kAttnWaves), dim3(64), 0, stream,
+                       static_cast<const uint16_t*>(q), static_cast<const u32x4*>(k_cache),
+                       static_cast<const u32x4*>(v_cache), hdr, list, ws_ml, ws_acc, Hq, Hkv, g,
+                       scale_log2e);
+    COPRIS_POST("attn_split_flat_kernel");
+    COPRIS_PRE("attn_merge_flat_kernel");
+    hipLaunchKernelGGL(attn_merge_flat_kernel<uint16_t>, dim3(C, Hq), dim3(D), 0, stream, hdr,
+                       seq_off, ws_ml, ws_acc, static_cast<uint16_t*>(out), lse, Hq, Hkv, g, D);
+    COPRIS_POST("attn_merge_flat_kernel");
+    return 0;
+  }
+
   COPRIS_PRE("attn_worklist_kernel");
   hipLaunchKernelGGL(attn_worklist_kernel, dim3(1), dim3(kListThreads), 0, stream, ctx_len, C,
                      max_tokens, hdr, seq_off, list);
   COPRIS_POST("attn_worklist_kernel");
-
-  const int64_t max_items = w.max_list * Hkv;
-  const bool tuned = dtype == 1 && D == kD && page_size == kP;
-  if (tuned) {
-    constexpr int kWavesPerCu = 8;
-    int grid = 256 * kWavesPerCu;
-    if (grid > max_items) grid = static_cast<int>(max_items);
-    COPRIS_PRE("attn_split_mfma_kernel");
-    hipLaunchKernelGGL(attn_split_mfma_kernel<3>, dim3(grid), dim3(64), 0, stream,
-                       static_cast<const uint16_t*>(q), static_cast<const u32x4*>(k_cache),
-                       static_cast<const u32x4*>(v_cache), block_table, ctx_len, hdr, list, ws_ml,
-                       ws_acc, Hq, Hkv, g, max_pages, max_tokens, scale_log2e);
-    COPRIS_POST("attn_split_mfma_kernel");
-  } else {
-    const dim3 grid(static_cast<unsigned>(max_items));
+  {
+    const dim3 grid(static_cast<unsigned>(w.max_list * Hkv));
 #define COPRIS_GENERIC(T, DD)                                                                   \
   hipLaunchKernelGGL((attn_split_generic_kernel<T, DD>), grid, dim3(256), 0, stream,            \
                      static_cast<const T*>(q), static_cast<const T*>(k_cache),                  \
@@ -527,7 +676,6 @@ int launch_decode_attn(const void* q, const void* k_cache, const void* v_cache,
 #undef COPRIS_GENERIC
     COPRIS_POST("attn_split_generic_kernel");
   }
-
   COPRIS_PRE("attn_merge_kernel");
   if (dtype == 0) {
     hipLaunchKernelGGL(attn_merge_kernel<float>, dim3(C, Hq), dim3(D), 0, stream, seq_off, ws_ml,
