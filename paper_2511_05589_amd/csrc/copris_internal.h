@@ -30,7 +30,7 @@ constexpr int kAttnWaves = 256 * 8;     // persistent wavefronts of the tuned sp
 struct AttnWorkspace {
   size_t hdr;       // int32[64]:  [0] number of (seq, chunk) entries, [1] work counter
   size_t seq_off;   // int32[C+1]: first list entry (generic path) / page prefix (tuned path) of every sequence
-  size_t list;      // int2[]: (seq, chunk) items (generic path) / flat slot entries (tuned path)
+  size_t list;      // int2[]: (seq, chunk) items (generic path) / int4 start cursor per wavefront (tuned path)
   size_t ml;        // float2[max_list*Hkv*g]: running max (log2 domain) and sum of weights
   size_t acc;       // float[max_list*Hkv*g*D]: un-normalised weighted value sums
   size_t total;

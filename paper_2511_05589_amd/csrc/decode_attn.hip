@@ -57,9 +57,9 @@ AttnWorkspace attn_workspace_layout(int C, int Hq, int Hkv, int D, int page_size
   const int64_t max_tokens = static_cast<int64_t>(max_pages) * page_size;
   const int64_t chunks = (max_tokens + kAttnChunkTokens - 1) / kAttnChunkTokens;
   w.max_list = static_cast<int64_t>(C) * (chunks > 0 ? chunks : 1);
-  // list: (seq, chunk) items of the generic path, or the flat slot list of the tuned path
-  const int64_t max_slots = static_cast<int64_t>(C) * max_pages * Hkv;
-  const int64_t list_len = w.max_list > max_slots ? w.max_list : max_slots;
+  // list: (seq, chunk) items of the generic path, or one int4 start cursor per wavefront of
+  // the tuned path
+  const int64_t list_len = w.max_list > 2 * kAttnWaves ? w.max_list : 2 * kAttnWaves;
   // partials: one per (item, kv head), or one per (wavefront, segment) overlap
   const int64_t part_a = w.max_list * Hkv;
   const int64_t part_b = static_cast<int64_t>(kAttnWaves) + static_cast<int64_t>(C) * Hkv;
@@ -265,10 +265,17 @@ constexpr int kD = 128;
 constexpr int kP = 16;
 constexpr int kPageGranules = kP * kD * 2 / 16;   // 256 16-byte granules per (page, kv head)
 
-// hdr[0] = slots in total, hdr[1] = slots per wavefront.  seq_pg[i] = pages of sequences < i.
+// The slot stream: for every sequence in batch order, for every kv head, the pages of the
+// context in order; one slot = one (page, kv head) = 16 tokens x 128 dims of K and of V.
+// Wavefront w of the split kernel takes the slots [w*share, (w+1)*share).
+// This kernel (one workgroup) writes
+//   seq_pg[i] = pages of the sequences before i (seq_pg[C] = all pages),
+//   hdr[0] = slots in total, hdr[1] = share,
+//   start[w] = {sequence, kv head, page index, pages of that sequence} of slot w*share
+//              (sequence = -1: no slots for this wavefront).
 __global__ __launch_bounds__(kListThreads) void attn_scan_kernel(
     const int32_t* __restrict__ ctx_len, int C, int max_tokens, int Hkv, int32_t* __restrict__ hdr,
-    int32_t* __restrict__ seq_pg) {
+    int32_t* __restrict__ seq_pg, int4* __restrict__ start) {
   __shared__ int s_wave[kListThreads / kWave];
   __shared__ int s_carry;
   const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
@@ -294,30 +301,32 @@ __global__ __launch_bounds__(kListThreads) void attn_scan_kernel(
     if (tid == kListThreads - 1) s_carry = before + incl;
     __syncthreads();
   }
+  const int pages = s_carry;
+  const int total = pages * Hkv;
+  const int share = total > 0 ? (total + kAttnWaves - 1) / kAttnWaves : 1;
   if (tid == 0) {
-    const int total = s_carry * Hkv;
-    seq_pg[C] = s_carry;
+    seq_pg[C] = pages;
     hdr[0] = total;
-    hdr[1] = total > 0 ? (total + kAttnWaves - 1) / kAttnWaves : 1;
+    hdr[1] = share;
   }
-}
-
-// Slot entry: x = physical page, y = (tokens valid in the page - 1) | kv head << 4 | sequence << 12.
-__global__ __launch_bounds__(256) void attn_fill_kernel(const int32_t* __restrict__ block_table,
-                                                        const int32_t* __restrict__ ctx_len,
-                                                        const int32_t* __restrict__ seq_pg,
-                                                        int2* __restrict__ entries, int Hkv,
-                                                        int max_pages, int max_tokens) {
-  const int seq = blockIdx.x;
-  int n = ctx_len[seq];
-  n = n < 0 ? 0 : (n > max_tokens ? max_tokens : n);
-  const int npg = (n + kP - 1) / kP;
-  const size_t base = static_cast<size_t>(seq_pg[seq]) * Hkv;
-  const int32_t* bt = block_table + static_cast<size_t>(seq) * max_pages;
-  for (int e = threadIdx.x; e < npg * Hkv; e += 256) {
-    const int kvh = e / npg, p = e - kvh * npg;
-    const int valid = min(kP, n - p * kP);
-    entries[base + e] = make_int2(bt[p], (valid - 1) | (kvh << 4) | (seq << 12));
+  __syncthreads();   // seq_pg[] (written above by this workgroup) is read below
+  for (int w = tid; w < kAttnWaves; w += kListThreads) {
+    const int64_t slot = static_cast<int64_t>(w) * share;
+    int4 st = make_int4(-1, 0, 0, 0);
+    if (slot < total) {
+      // the last sequence whose first slot is <= slot (empty sequences share their
+      // successor's first slot and are skipped by taking the last)
+      int lo = 0, hi = C - 1;
+      while (lo < hi) {
+        const int mid = (lo + hi + 1) >> 1;
+        if (static_cast<int64_t>(seq_pg[mid]) * Hkv <= slot) lo = mid; else hi = mid - 1;
+      }
+      const int pg0 = seq_pg[lo];
+      const int npg = (lo + 1 < C ? seq_pg[lo + 1] : pages) - pg0;
+      const int r = static_cast<int>(slot - static_cast<int64_t>(pg0) * Hkv);
+      st = make_int4(lo, r / npg, r % npg, npg);
+    }
+    start[w] = st;
   }
 }
 
@@ -352,9 +361,10 @@ __device__ __forceinline__ int swz_v(int row, int c) { return row * 16 + (c ^ ((
 template <int NS>
 __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2))) void attn_split_flat_kernel(
     const uint16_t* __restrict__ q, const u32x4* __restrict__ k_cache,
-    const u32x4* __restrict__ v_cache, const int32_t* __restrict__ hdr,
-    const int2* __restrict__ entries, float2* __restrict__ ws_ml, float* __restrict__ ws_acc,
-    int Hq, int Hkv, int g, float scale_log2e) {
+    const u32x4* __restrict__ v_cache, const int32_t* __restrict__ block_table,
+    const int32_t* __restrict__ ctx_len, const int32_t* __restrict__ hdr,
+    const int4* __restrict__ start, float2* __restrict__ ws_ml, float* __restrict__ ws_acc, int C,
+    int Hq, int Hkv, int g, int max_pages, int max_tokens, float scale_log2e) {
   __shared__ u32x4 lds_k[kPageGranules];
   __shared__ u32x4 lds_v[kPageGranules];
   const int lane = threadIdx.x;
@@ -362,10 +372,33 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2))) void
   const int b = lane >> 4;        // k-group of the MFMA operand layouts
   const int total = hdr[0], share = hdr[1];
   const int wv = blockIdx.x;
+  const int4 st = start[wv];
+  if (st.x < 0) return;
   const int64_t first = static_cast<int64_t>(wv) * share;
-  if (first >= total) return;
   const int n = static_cast<int>(min(static_cast<int64_t>(share), total - first));   // slots of this wavefront
-  const int2* __restrict__ ent = entries + first;
+
+  // Fetch cursor over the slot stream (all wave-uniform): the next slot to request is page
+  // f_p of (sequence f_seq, kv head f_kvh); f_page is its physical page, read one slot ahead
+  // so that the table look-up is off the refill's path.
+  int f_seq = st.x, f_kvh = st.y, f_p = st.z, f_npg = st.w;
+  int f_ctx = min(max(ctx_len[f_seq], 0), max_tokens);
+  int f_page = block_table[static_cast<size_t>(f_seq) * max_pages + f_p];
+  auto next_entry = [&](int& page, int& code) __attribute__((always_inline)) {
+    page = f_page;
+    code = (min(kP, f_ctx - f_p * kP) - 1) | (f_kvh << 4) | (f_seq << 12);
+    if (++f_p == f_npg) {
+      f_p = 0;
+      if (++f_kvh == Hkv) {   // on to the next sequence that has a context
+        f_kvh = 0;
+        f_npg = 0;
+        while (f_npg == 0 && ++f_seq < C) {
+          f_ctx = min(max(ctx_len[f_seq], 0), max_tokens);
+          f_npg = (f_ctx + kP - 1) / kP;
+        }
+      }
+    }
+    f_page = f_seq < C ? block_table[static_cast<size_t>(f_seq) * max_pages + f_p] : 0;
+  };
 
   // state of the segment (sequence, kv head) being accumulated
   int cur_seg = -1;
@@ -425,9 +458,9 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2))) void
       lds_v[swz_v(4 * j + b, head)] = r.v[j];
     }
     if (kSteady || i + NS < n) {
-      const int2 e = ent[i + NS];
-      code = e.y;
-      load_page(r, k_cache, v_cache, e.x, Hkv, (e.y >> 4) & 255, lane);
+      int page;
+      next_entry(page, code);
+      load_page(r, k_cache, v_cache, page, Hkv, (code >> 4) & 255, lane);
     }
     __syncthreads();
 
@@ -486,20 +519,20 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2))) void
   int c0 = 0, c1 = 0, c2 = 0;   // entry words of the slots held in st0..st2
   int i = 0;
   {
-    const int2 e = ent[0];
-    c0 = e.y;
-    load_page(st0, k_cache, v_cache, e.x, Hkv, (e.y >> 4) & 255, lane);
+    int page;
+    next_entry(page, c0);
+    load_page(st0, k_cache, v_cache, page, Hkv, (c0 >> 4) & 255, lane);
   }
   if (n >= 2 * NS) {
     {
-      const int2 e = ent[1];
-      c1 = e.y;
-      load_page(st1, k_cache, v_cache, e.x, Hkv, (e.y >> 4) & 255, lane);
+      int page;
+      next_entry(page, c1);
+      load_page(st1, k_cache, v_cache, page, Hkv, (c1 >> 4) & 255, lane);
     }
     {
-      const int2 e = ent[2];
-      c2 = e.y;
-      load_page(st2, k_cache, v_cache, e.x, Hkv, (e.y >> 4) & 255, lane);
+      int page;
+      next_entry(page, c2);
+      load_page(st2, k_cache, v_cache, page, Hkv, (c2 >> 4) & 255, lane);
     }
     do {   // steady state: every refill exists
       do_slot(st0, c0, i, std::true_type{});
@@ -509,14 +542,14 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2))) void
     } while (i + 2 * NS <= n);
   } else {
     if (1 < n) {
-      const int2 e = ent[1];
-      c1 = e.y;
-      load_page(st1, k_cache, v_cache, e.x, Hkv, (e.y >> 4) & 255, lane);
+      int page;
+      next_entry(page, c1);
+      load_page(st1, k_cache, v_cache, page, Hkv, (c1 >> 4) & 255, lane);
     }
     if (2 < n) {
-      const int2 e = ent[2];
-      c2 = e.y;
-      load_page(st2, k_cache, v_cache, e.x, Hkv, (e.y >> 4) & 255, lane);
+      int page;
+      next_entry(page, c2);
+      load_page(st2, k_cache, v_cache, page, Hkv, (c2 >> 4) & 255, lane);
     }
   }
   for (; i < n; i += NS) {   // the last 3..5 slots of the share (or a short share)
@@ -582,35 +615,51 @@ __global__ void attn_merge_kernel(const int32_t* __restrict__ seq_off,
 // Merge for the flat slot stream: segment (seq, kv head) occupies slots [a, a+npg) and was
 // touched by the wavefronts a/share .. (a+npg-1)/share; the partial of (wavefront w,
 // segment s) sits at index w + s.
-template <typename T>
-__global__ void attn_merge_flat_kernel(const int32_t* __restrict__ hdr,
-                                       const int32_t* __restrict__ seq_pg,
-                                       const float2* __restrict__ ws_ml,
-                                       const float* __restrict__ ws_acc, T* __restrict__ out,
-                                       float* __restrict__ lse, int Hq, int Hkv, int g, int D) {
-  const int seq = blockIdx.x, hq = blockIdx.y, d = threadIdx.x;
-  const int kvh = hq / g, h = hq - kvh * g;
+__global__ __launch_bounds__(256) void attn_merge_flat_kernel(const int32_t* __restrict__ hdr,
+                                                              const int32_t* __restrict__ seq_pg,
+                                                              const float2* __restrict__ ws_ml,
+                                                              const float* __restrict__ ws_acc,
+                                                              uint16_t* __restrict__ out,
+                                                              float* __restrict__ lse, int Hq, int Hkv,
+                                                              int g) {
+  // one workgroup per (sequence, kv head); a thread owns four head_dim indices of one head
+  const int seq = blockIdx.x, kvh = blockIdx.y;
   const int share = hdr[1];
   const int npg = seq_pg[seq + 1] - seq_pg[seq];
   const int64_t a = static_cast<int64_t>(seq_pg[seq]) * Hkv + static_cast<int64_t>(kvh) * npg;
   const int seg = seq * Hkv + kvh;
   const int w0 = npg > 0 ? static_cast<int>(a / share) : 0;
   const int n = npg > 0 ? static_cast<int>((a + npg - 1) / share) - w0 + 1 : 0;
-  const size_t slot0 = (static_cast<size_t>(w0) + seg) * g + h;   // consecutive wavefronts: stride g
-  float m_star = -INFINITY;
-  for (int e = 0; e < n; ++e) m_star = fmaxf(m_star, ws_ml[slot0 + static_cast<size_t>(e) * g].x);
-  float denom = 0.0f, num = 0.0f;
-  for (int e = 0; e < n; ++e) {
-    const size_t slot = slot0 + static_cast<size_t>(e) * g;
-    const float2 ml = ws_ml[slot];
-    const float w = __builtin_amdgcn_exp2f(ml.x - m_star);
-    denom = fmaf(w, ml.y, denom);
-    num = fmaf(w, ws_acc[slot * D + d], num);
+  for (int idx = threadIdx.x; idx < g * (kD / 4); idx += 256) {
+    const int h = idx / (kD / 4), d4 = idx - h * (kD / 4);
+    const size_t slot0 = (static_cast<size_t>(w0) + seg) * g + h;   // consecutive wavefronts: stride g
+    float m_star = -INFINITY;
+    for (int e = 0; e < n; ++e) m_star = fmaxf(m_star, ws_ml[slot0 + static_cast<size_t>(e) * g].x);
+    float denom = 0.0f;
+    float4 num = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+    for (int e = 0; e < n; ++e) {
+      const size_t slot = slot0 + static_cast<size_t>(e) * g;
+      const float2 ml = ws_ml[slot];
+      const float4 x = *reinterpret_cast<const float4*>(ws_acc + slot * kD + 4 * d4);
+      const float w = __builtin_amdgcn_exp2f(ml.x - m_star);
+      denom = fmaf(w, ml.y, denom);
+      num.x = fmaf(w, x.x, num.x);
+      num.y = fmaf(w, x.y, num.y);
+      num.z = fmaf(w, x.z, num.z);
+      num.w = fmaf(w, x.w, num.w);
+    }
+    const size_t oh = static_cast<size_t>(seq) * Hq + kvh * g + h;
+    ushort4 r = make_ushort4(0, 0, 0, 0);
+    if (n > 0) {
+      r.x = f32_to_bf16(num.x / denom);
+      r.y = f32_to_bf16(num.y / denom);
+      r.z = f32_to_bf16(num.z / denom);
+      r.w = f32_to_bf16(num.w / denom);
+    }
+    *reinterpret_cast<ushort4*>(out + oh * kD + 4 * d4) = r;
+    if (lse != nullptr && d4 == 0)
+      lse[oh] = n > 0 ? (m_star + __builtin_amdgcn_logf(denom)) * kLn2 : -INFINITY;
   }
-  const size_t oh = static_cast<size_t>(seq) * Hq + hq;
-  store_out<T>(out + oh * D + d, n > 0 ? num / denom : 0.0f);
-  if (lse != nullptr && d == 0)
-    lse[oh] = n > 0 ? (m_star + __builtin_amdgcn_logf(denom)) * kLn2 : -INFINITY;
 }
 
 // --------------------------------------------------------------------------
@@ -636,23 +685,20 @@ int launch_decode_attn(const void* q, const void* k_cache, const void* v_cache,
   const bool tuned = dtype == 1 && D == kD && page_size == kP && Hkv <= 256 && C < (1 << 19) &&
                      static_cast<int64_t>(C) * max_pages * Hkv < (1ll << 31);
   if (tuned) {
+    int4* start = reinterpret_cast<int4*>(list);   // kAttnWaves start cursors (the list area is larger)
     COPRIS_PRE("attn_scan_kernel");
     hipLaunchKernelGGL(attn_scan_kernel, dim3(1), dim3(kListThreads), 0, stream, ctx_len, C,
-                       max_tokens, Hkv, hdr, seq_off);
+                       max_tokens, Hkv, hdr, seq_off, start);
     COPRIS_POST("attn_scan_kernel");
-    COPRIS_PRE("attn_fill_kernel");
-    hipLaunchKernelGGL(attn_fill_kernel, dim3(C), dim3(256), 0, stream, block_table, ctx_len,
-                       seq_off, list, Hkv, max_pages, max_tokens);
-    COPRIS_POST("attn_fill_kernel");
     COPRIS_PRE("attn_split_flat_kernel");
     hipLaunchKernelGGL(attn_split_flat_kernel<3>, dim3(kAttnWaves), dim3(64), 0, stream,
                        static_cast<const uint16_t*>(q), static_cast<const u32x4*>(k_cache),
-                       static_cast<const u32x4*>(v_cache), hdr, list, ws_ml, ws_acc, Hq, Hkv, g,
-                       scale_log2e);
+                       static_cast<const u32x4*>(v_cache), block_table, ctx_len, hdr, start, ws_ml,
+                       ws_acc, C, Hq, Hkv, g, max_pages, max_tokens, scale_log2e);
     COPRIS_POST("attn_split_flat_kernel");
     COPRIS_PRE("attn_merge_flat_kernel");
-    hipLaunchKernelGGL(attn_merge_flat_kernel<uint16_t>, dim3(C, Hq), dim3(D), 0, stream, hdr,
-                       seq_off, ws_ml, ws_acc, static_cast<uint16_t*>(out), lse, Hq, Hkv, g, D);
+    hipLaunchKernelGGL(attn_merge_flat_kernel, dim3(C, Hkv), dim3(256), 0, stream, hdr, seq_off,
+                       ws_ml, ws_acc, static_cast<uint16_t*>(out), lse, Hq, Hkv, g);
     COPRIS_POST("attn_merge_flat_kernel");
     return 0;
   }

@@ -71,6 +71,29 @@ def test_page_permutation_is_bitwise_invariant_and_runs_are_reproducible(R):
     np.testing.assert_array_equal(lse1, lse2)
 
 
+def test_batch_order_equivariance_and_chunking_independence(R):
+    # permuting the batch rows permutes the outputs; the split along the context depends on
+    # the position in the batch, so equality is to rounding, not bitwise
+    ctx = [1000, 37, 1536, 513, 16, 2500, 800, 64]
+    case = W.make_small_decode_case(21, len(ctx), 28, 4, 128, W.BF16, 16, ctx)
+    out1, lse1 = R.run_decode_attn(case, W.BF16)
+    perm = np.random.default_rng(2).permutation(len(ctx))
+    c2 = dict(case)
+    for k in ("q", "block_table", "ctx_len"):
+        c2[k] = case[k][perm]
+    out2, lse2 = R.run_decode_attn(c2, W.BF16)
+    assert np.abs(out1[perm] - out2).max() <= 2 ** -6          # one bf16 ulp at |x| < 4
+    np.testing.assert_allclose(lse1[perm], lse2, atol=1e-5)
+
+
+def test_single_head_group_and_many_short_sequences(R):
+    # g = 1 (no grouping) and more sequences than pages per share
+    rng = np.random.default_rng(3)
+    ctx = rng.integers(1, 40, size=300).tolist()
+    case = W.make_small_decode_case(22, len(ctx), 4, 4, 128, W.BF16, 16, ctx)
+    _run_case(R, case, W.BF16, "g=1 short")
+
+
 def test_large_scores_do_not_overflow(R):
     case = W.make_small_decode_case(8, 2, 7, 1, 128, W.BF16, 16, [600, 31], poison=True)
     q = W.to_f32(case["q"], W.BF16) * 40.0           # scores of magnitude ~ 10^2..10^3 * scale

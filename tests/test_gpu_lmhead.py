@@ -27,7 +27,10 @@ def test_tiny_config_fp32(R):
 
 @pytest.mark.parametrize("dtype", [W.F32, W.BF16])
 @pytest.mark.parametrize("C,H,V", [(1, 64, 50), (3, 256, 1000), (17, 512, 4099), (64, 1536, 9000),
-                                   (256, 128, 2500), (33, 3584, 777)])
+                                   (256, 128, 2500), (33, 3584, 777),
+                                   (300, 512, 3001),      # two batch blocks, ragged vocabulary tail
+                                   (129, 192, 70000),     # more tiles than persistent workgroups
+                                   (5, 72, 260)])         # hidden size the matrix-core kernel does not take
 def test_small_shapes(R, dtype, C, H, V):
     inp = W.make_small_lmhead_case(C * 7 + V, C, H, V, dtype, w_std=0.05)
     tok, lp, lse = R.run_lmhead_logprob(inp, dtype)
