@@ -225,3 +225,70 @@ def is_ratio(logp_cur, logp_buf, logp_roll, cu_seqlens, split, mask, eps_low, ep
         seq_nclip[b] = int((rc[counted] != r[counted]).sum())
     return {"ratio": ratio, "ratio_clipped": clipped, "seq_sum": seq_sum,
             "seq_cnt": seq_cnt, "seq_nclip": seq_nclip}
+
+
+# --------------------------------------------------------------------------
+# GRPO clipped surrogate on the cross-stage ratio (Section 3.1, Eq. 2-4).
+# --------------------------------------------------------------------------
+def grpo_surrogate(logp_cur, logp_buf, logp_roll, cu_seqlens, split, mask, adv, eps_low, eps_high):
+    """Eq. 3 per token, on the ratio of Eq. 8, and the two aggregations of Eq. 2 / Table 4.
+
+    The old-policy log-prob of a token is selected exactly as in `is_ratio`
+    (buffered prefix of split[b] tokens, then this stage's rollout).  adv[b] is
+    the group-normalised advantage of Eq. 4: one number per trajectory, the same
+    for all of its tokens.  For a counted token of sequence b
+
+        r  = exp(cur - old)                          (Eq. 8)
+        rc = min(max(r, 1-eps_low), 1+eps_high)      (clip of Eq. 3; Table 4: 0.2 / 0.28)
+        t1 = r * adv[b],  t2 = rc * adv[b]
+        surr = t1 if t1 <= t2 else t2                (Eq. 3: the smaller of the two terms)
+        grad = t1 if t1 <= t2 else 0                 (d surr / d cur: dr/dcur = r, and the
+                                                      clipped term is constant wherever it
+                                                      differs from the unclipped one)
+
+    A masked token gives 0 in both outputs and is not counted.  Aggregations:
+    token mean (Table 4, "loss aggregation mode"): sum of surr over all counted
+    tokens / number of counted tokens; sequence mean (Eq. 2): mean over the B
+    sequences of (sum of surr over the sequence's counted tokens / their number),
+    a sequence without counted tokens contributing 0.  Table 4 sets the KL
+    coefficient to 0, so Eq. 2's KL term is absent.
+
+    Returns surr [N], grad [N], seq_surr [B], seq_cnt [B], obj_token_mean, obj_seq_mean.
+    """
+    cur = np.asarray(logp_cur, dtype=np.float64)
+    buf = np.asarray(logp_buf, dtype=np.float64)
+    roll = np.asarray(logp_roll, dtype=np.float64)
+    cu = np.asarray(cu_seqlens, dtype=np.int64)
+    A = np.asarray(adv, dtype=np.float64)
+    B = cu.size - 1
+    N = cur.size
+    surr = np.zeros(N)
+    grad = np.zeros(N)
+    seq_surr = np.zeros(B)
+    seq_cnt = np.zeros(B, dtype=np.int64)
+    lo = 1.0 - float(eps_low)
+    hi = 1.0 + float(eps_high)
+    for b in range(B):
+        s, e = int(cu[b]), int(cu[b + 1])
+        if e <= s:
+            continue
+        k = min(max(int(split[b]), 0), e - s)
+        old = np.concatenate([buf[s:s + k], roll[s + k:e]])
+        counted = np.ones(e - s, dtype=bool) if mask is None else (np.asarray(mask[s:e]) != 0)
+        with np.errstate(over="ignore", invalid="ignore"):
+            r = np.exp(cur[s:e] - old)
+            rc = np.minimum(np.maximum(r, lo), hi)
+            t1 = r * A[b]
+            t2 = rc * A[b]
+            unclipped = t1 <= t2
+        tok = np.where(unclipped, t1, t2)
+        surr[s:e] = np.where(counted, tok, 0.0)
+        grad[s:e] = np.where(counted & unclipped, t1, 0.0)
+        seq_surr[b] = tok[counted].sum()
+        seq_cnt[b] = int(counted.sum())
+    total = int(seq_cnt.sum())
+    obj_token_mean = float(seq_surr.sum() / total) if total > 0 else 0.0
+    per_seq = np.where(seq_cnt > 0, seq_surr / np.maximum(seq_cnt, 1), 0.0)
+    obj_seq_mean = float(per_seq.sum() / B) if B > 0 else 0.0
+    return {"surr": surr, "grad": grad, "seq_surr": seq_surr, "seq_cnt": seq_cnt,
+            "obj_token_mean": obj_token_mean, "obj_seq_mean": obj_seq_mean}

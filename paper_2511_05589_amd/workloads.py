@@ -373,7 +373,12 @@ def make_is_inputs(cfg: ISConfig, *, rng: Optional[np.random.Generator] = None,
     if poison:
         # masked-out inputs must not leak either
         logp_cur = np.where(mask == 1, logp_cur, np.float32(np.nan)).astype(np.float32)
+    # One advantage per trajectory, drawn last so that the arrays above do not depend on
+    # it: standard normal (group-normalised advantages have zero mean and unit
+    # variance), every eighth exactly 0 (a group whose samples all earned the same reward).
+    adv = rng.normal(0.0, 1.0, size=cfg.B).astype(np.float32)
+    adv[rng.random(cfg.B) < 0.125] = 0.0
     return {"cfg": cfg, "B": cfg.B, "N": N, "lens": lens.astype(np.int32),
             "cu_seqlens": cu.astype(np.int32), "split": split, "mask": mask,
             "logp_cur": logp_cur, "logp_buf": logp_buf, "logp_roll": logp_roll,
-            "eps_low": cfg.eps_low, "eps_high": cfg.eps_high}
+            "adv": adv, "eps_low": cfg.eps_low, "eps_high": cfg.eps_high}
