@@ -219,6 +219,22 @@ def main():
         "all_kernel_ms": {k: round(v, 4) for k, v in kernel_ms.items()},
         "input_generation_s": round(t_gen, 1),
     }
+    # ---- outside the step: the GRPO clipped surrogate on the same IS batch (a row added
+    # after the decode path; same 17 algorithmic bytes per token as the ratio kernel) ----
+    gd = runner.stage_grpo_surrogate(isb, dev)
+    for _ in range(3):
+        gd.run(stream)
+    torch.cuda.synchronize()
+    g0, g1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    g0.record(stream)
+    for _ in range(args.steps):
+        gd.run(stream)
+    g1.record(stream)
+    torch.cuda.synchronize()
+    grpo_ms = g0.elapsed_time(g1) / args.steps
+    result["extras"] = {"grpo_surrogate": {"call_ms": round(grpo_ms, 4), "algorithmic_bytes": ab["is"],
+                                           "achieved_GBps": round(ab["is"] / (grpo_ms * 1e-3) / 1e9, 1),
+                                           "workload": f"IS batch of {isb['B']} trajectories, {isb['N']} tokens"}}
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(cfg, inp, args.cpu_sample)
     print(json.dumps(result))

@@ -184,6 +184,49 @@ int copris_is_ratio(const float* logp_cur, const float* logp_buf, const float* l
                     float* seq_sum, int32_t* seq_cnt, int32_t* seq_nclip,
                     int B, int64_t N, void* stream);
 
+/* ------------------------------------------------------------------------
+ * GRPO clipped surrogate on the cross-stage ratio, over the same packed batch.
+ *
+ * Section 3.1, Eq. 3: L = min(r A, clip(r, 1-eps_low, 1+eps_high) A) per token,
+ * with r the ratio of Eq. 8 (old-policy log-prob selected by split[b] exactly as
+ * in copris_is_ratio) and A = adv[b] the group-normalised advantage of Eq. 4, one
+ * number per trajectory.  For a counted token:
+ *
+ *   t1 = r * adv[b];  t2 = clip(r) * adv[b]
+ *   surr[j] = t1 <= t2 ? t1 : t2
+ *   grad[j] = t1 <= t2 ? t1 : 0        d surr[j] / d logp_cur[j]  (dr/dlogp_cur = r; the
+ *                                      clipped term is constant where it differs from r)
+ *   seq_surr[b] += surr[j]; seq_cnt[b] += 1
+ *
+ * A masked token gives surr = grad = 0 and is not counted.  Then
+ *
+ *   objective[0] = sum_b seq_surr[b] / sum_b seq_cnt[b]       token mean (Table 4,
+ *                                                             "loss aggregation mode")
+ *   objective[1] = (1/B) sum_b seq_surr[b] / seq_cnt[b]       Eq. 2: mean over the
+ *                  sequences of the per-sequence mean; a sequence without counted
+ *                  tokens contributes 0
+ *
+ * Both are to be maximised (the loss is their negative); Table 4 sets the KL
+ * coefficient to 0, so Eq. 2's KL term is absent.  grad is not divided by any
+ * count: the gradient of objective[0] with respect to logp_cur[j] is
+ * grad[j] / sum_b seq_cnt[b].  No clamp before the exponential; comparisons with
+ * NaN are false (a NaN ratio gives surr = t2 = NaN, grad = 0).  Sums are formed in
+ * a fixed order (bitwise reproducible); the two objectives are accumulated in fp64.
+ *
+ *   logp_cur, logp_buf, logp_roll [N] fp32      cu_seqlens [B+1] int32, cu[0]=0, cu[B]=N
+ *   split [B] int32 in 0..len_b                 mask [N] uint8 or NULL (all counted)
+ *   adv [B] fp32                                surr, grad [N] fp32 out
+ *   seq_surr [B] fp32, seq_cnt [B] int32 out    objective [2] fp32 out
+ *
+ * Requires 0 <= eps_low < 1, eps_high >= 0, B >= 0, 0 <= N < 2^31; the [N] arrays
+ * and mask 16-byte aligned.  B == 0 writes objective = {0, 0}.
+ * ------------------------------------------------------------------------ */
+int copris_grpo_surrogate(const float* logp_cur, const float* logp_buf, const float* logp_roll,
+                          const int32_t* cu_seqlens, const int32_t* split, const uint8_t* mask,
+                          const float* adv, float eps_low, float eps_high,
+                          float* surr, float* grad, float* seq_surr, int32_t* seq_cnt,
+                          float* objective, int B, int64_t N, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -35,6 +35,8 @@ SIGNATURES = {
                               + [c_size_t] + [c_int] * 4 + [c_void_p]),
     "copris_is_ratio": (c_int, [c_void_p] * 6 + [c_float, c_float] + [c_void_p] * 5
                         + [c_int, c_int64, c_void_p]),
+    "copris_grpo_surrogate": (c_int, [c_void_p] * 7 + [c_float, c_float] + [c_void_p] * 5
+                              + [c_int, c_int64, c_void_p]),
 }
 
 _lib = None
@@ -154,3 +156,15 @@ def is_ratio(logp_cur, logp_buf, logp_roll, cu_seqlens, split, mask, ratio, rati
         float(eps_low), float(eps_high), _ptr(ratio), _ptr(ratio_clipped), _ptr(seq_sum),
         _ptr(seq_cnt), _ptr(seq_nclip), B, N, _stream(stream))
     _check(code, "copris_is_ratio")
+
+
+def grpo_surrogate(logp_cur, logp_buf, logp_roll, cu_seqlens, split, mask, adv, surr, grad, seq_surr,
+                   seq_cnt, objective, *, eps_low: float, eps_high: float, stream=None) -> None:
+    """copris_grpo_surrogate on device tensors."""
+    B = cu_seqlens.numel() - 1
+    N = logp_cur.numel()
+    code = load_library().copris_grpo_surrogate(
+        _ptr(logp_cur), _ptr(logp_buf), _ptr(logp_roll), _ptr(cu_seqlens), _ptr(split), _ptr(mask),
+        _ptr(adv), float(eps_low), float(eps_high), _ptr(surr), _ptr(grad), _ptr(seq_surr),
+        _ptr(seq_cnt), _ptr(objective), B, N, _stream(stream))
+    _check(code, "copris_grpo_surrogate")

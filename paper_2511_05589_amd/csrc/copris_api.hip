@@ -142,4 +142,25 @@ int copris_is_ratio(const float* logp_cur, const float* logp_buf, const float* l
                           static_cast<hipStream_t>(stream));
 }
 
+int copris_grpo_surrogate(const float* logp_cur, const float* logp_buf, const float* logp_roll,
+                          const int32_t* cu_seqlens, const int32_t* split, const uint8_t* mask,
+                          const float* adv, float eps_low, float eps_high, float* surr, float* grad,
+                          float* seq_surr, int32_t* seq_cnt, float* objective, int B, int64_t N,
+                          void* stream) {
+  if (B < 0 || N < 0 || N >= (1ll << 31)) return COPRIS_EINVAL;
+  if (!(eps_low >= 0.0f) || !(eps_low < 1.0f) || !(eps_high >= 0.0f) || !(eps_high < INFINITY))
+    return COPRIS_EINVAL;
+  if (!objective) return COPRIS_EINVAL;
+  if (B == 0 && N != 0) return COPRIS_EINVAL;
+  if (B > 0 && (!cu_seqlens || !split || !adv || !seq_surr || !seq_cnt)) return COPRIS_EINVAL;
+  if (N > 0 && (!logp_cur || !logp_buf || !logp_roll || !surr || !grad)) return COPRIS_EINVAL;
+  if (!aligned16(logp_cur) || !aligned16(logp_buf) || !aligned16(logp_roll) || !aligned16(surr) ||
+      !aligned16(grad) || (mask && !aligned16(mask)))
+    return COPRIS_EINVAL;
+  (void)hipGetLastError();
+  return copris::launch_grpo_surrogate(logp_cur, logp_buf, logp_roll, cu_seqlens, split, mask, adv,
+                                       eps_low, eps_high, surr, grad, seq_surr, seq_cnt, objective, B,
+                                       static_cast<hipStream_t>(stream));
+}
+
 }  // extern "C"

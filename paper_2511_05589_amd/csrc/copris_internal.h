@@ -62,5 +62,10 @@ int launch_is_ratio(const float* logp_cur, const float* logp_buf, const float* l
                     float eps_low, float eps_high, float* ratio, float* ratio_clipped,
                     float* seq_sum, int32_t* seq_cnt, int32_t* seq_nclip, int B,
                     hipStream_t stream);
+int launch_grpo_surrogate(const float* logp_cur, const float* logp_buf, const float* logp_roll,
+                          const int32_t* cu_seqlens, const int32_t* split, const uint8_t* mask,
+                          const float* adv, float eps_low, float eps_high, float* surr, float* grad,
+                          float* seq_surr, int32_t* seq_cnt, float* objective, int B,
+                          hipStream_t stream);
 
 }  // namespace copris

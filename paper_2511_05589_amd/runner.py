@@ -174,3 +174,53 @@ def run_is_ratio(b: dict, use_mask: bool = True) -> dict:
     return {"ratio": d.ratio.cpu().numpy()[:N], "ratio_clipped": d.ratio_clipped.cpu().numpy()[:N],
             "seq_sum": d.seq_sum.cpu().numpy()[:B], "seq_cnt": d.seq_cnt.cpu().numpy()[:B],
             "seq_nclip": d.seq_nclip.cpu().numpy()[:B]}
+
+
+@dataclass
+class GrpoDevice:
+    logp_cur: torch.Tensor
+    logp_buf: torch.Tensor
+    logp_roll: torch.Tensor
+    cu_seqlens: torch.Tensor
+    split: torch.Tensor
+    mask: Optional[torch.Tensor]
+    adv: torch.Tensor
+    surr: torch.Tensor
+    grad: torch.Tensor
+    seq_surr: torch.Tensor
+    seq_cnt: torch.Tensor
+    objective: torch.Tensor
+    eps_low: float
+    eps_high: float
+
+    def run(self, stream=None):
+        binding.grpo_surrogate(self.logp_cur, self.logp_buf, self.logp_roll, self.cu_seqlens,
+                               self.split, self.mask, self.adv, self.surr, self.grad, self.seq_surr,
+                               self.seq_cnt, self.objective, eps_low=self.eps_low,
+                               eps_high=self.eps_high, stream=stream)
+
+
+def stage_grpo_surrogate(b: dict, device=None, use_mask: bool = True) -> GrpoDevice:
+    device = device or require_gpu()
+    N, B = int(b["N"]), int(b["B"])
+    f = lambda k: to_device(np.asarray(b[k], dtype=np.float32), device=device)
+    mask = to_device(np.asarray(b["mask"], dtype=np.uint8), device=device) if (
+        use_mask and b.get("mask") is not None) else None
+    nanf = lambda n: torch.full((max(n, 1),), float("nan"), dtype=torch.float32, device=device)
+    return GrpoDevice(f("logp_cur"), f("logp_buf"), f("logp_roll"),
+                      to_device(np.asarray(b["cu_seqlens"], dtype=np.int32), device=device),
+                      to_device(np.asarray(b["split"], dtype=np.int32), device=device), mask,
+                      f("adv") if B > 0 else nanf(1), nanf(N), nanf(N), nanf(B),
+                      torch.full((max(B, 1),), -7, dtype=torch.int32, device=device), nanf(2),
+                      float(b["eps_low"]), float(b["eps_high"]))
+
+
+def run_grpo_surrogate(b: dict, use_mask: bool = True) -> dict:
+    d = stage_grpo_surrogate(b, use_mask=use_mask)
+    d.run()
+    torch.cuda.synchronize()
+    N, B = int(b["N"]), int(b["B"])
+    obj = d.objective.cpu().numpy()
+    return {"surr": d.surr.cpu().numpy()[:N], "grad": d.grad.cpu().numpy()[:N],
+            "seq_surr": d.seq_surr.cpu().numpy()[:B], "seq_cnt": d.seq_cnt.cpu().numpy()[:B],
+            "obj_token_mean": float(obj[0]), "obj_seq_mean": float(obj[1])}

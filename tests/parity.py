@@ -100,3 +100,58 @@ def check_is(got, ref, b, use_mask=True, what=""):
     assert (np.abs(got["seq_nclip"].astype(np.int64) - ref["seq_nclip"]) <= slack).all(), what
     srel = np.abs(got["seq_sum"].astype(np.float64) - ref["seq_sum"]) / np.maximum(ref["seq_sum"], 1.0)
     assert srel.max(initial=0.0) <= RATIO_RTOL, f"{what}: seq_sum rel error {srel.max():.3e}"
+
+
+# ---- GRPO clipped surrogate -------------------------------------------------
+SURR_RTOL = 1e-5      # same bar as the ratios the terms are built from
+
+
+def oracle_grpo(b, use_mask=True):
+    return O.grpo_surrogate(b["logp_cur"], b["logp_buf"], b["logp_roll"], b["cu_seqlens"], b["split"],
+                            b["mask"] if use_mask else None, b["adv"], b["eps_low"], b["eps_high"])
+
+
+def check_grpo(got, ref, b, use_mask=True, what=""):
+    """Per-token terms to SURR_RTOL relative; the branch of the min is a decision that fp32
+    and fp64 may take differently only where the ratio sits on a clip bound (then either
+    branch's gradient is accepted); counts exact; sums relative to the sum of magnitudes."""
+    N, B = int(b["N"]), int(b["B"])
+    counted = (np.asarray(b["mask"]) != 0) if (use_mask and b.get("mask") is not None) else np.ones(N, bool)
+    cu = np.asarray(b["cu_seqlens"], dtype=np.int64)
+    lens = np.diff(cu)
+    in_seq = np.zeros(N, dtype=bool)
+    for s in range(B):
+        in_seq[cu[s]:cu[s + 1]] = True
+    counted = counted & in_seq
+    A_tok = np.zeros(N)
+    A_tok[in_seq] = np.repeat(np.asarray(b["adv"], dtype=np.float64), lens)
+    ir = O.is_ratio(b["logp_cur"], b["logp_buf"], b["logp_roll"], b["cu_seqlens"], b["split"],
+                    b["mask"] if use_mask else None, b["eps_low"], b["eps_high"])
+    r = ir["ratio"]
+    lo, hi = 1.0 - b["eps_low"], 1.0 + b["eps_high"]
+    border = counted & ((np.abs(r - lo) <= 1e-6 * lo) | (np.abs(r - hi) <= 1e-6 * hi))
+    for key in ("surr", "grad"):
+        g = got[key].astype(np.float64)
+        assert (g[in_seq & ~counted] == 0.0).all(), f"{what}: {key} not 0 at masked tokens"
+    gs, rs = got["surr"].astype(np.float64)[counted], ref["surr"][counted]
+    fin = np.isfinite(rs)
+    assert (gs[~fin] == rs[~fin]).all() or np.isnan(rs[~fin]).all(), f"{what}: non-finite surr differs"
+    err = np.abs(gs[fin] - rs[fin])
+    assert (err <= SURR_RTOL * np.abs(rs[fin]) + 1e-30).all(), f"{what}: surr rel error {(err / np.maximum(np.abs(rs[fin]), 1e-300)).max():.3e}"
+    gg, rg = got["grad"].astype(np.float64), ref["grad"]
+    t1 = r * A_tok
+    ok = np.abs(gg - rg) <= SURR_RTOL * np.abs(rg) + 1e-30
+    either = border & ((gg == 0.0) | (np.abs(gg - t1) <= SURR_RTOL * np.abs(t1) + 1e-30))
+    bad = counted & np.isfinite(rg) & ~(ok | either)
+    assert not bad.any(), f"{what}: grad differs at {np.flatnonzero(bad)[:5]}"
+    np.testing.assert_array_equal(got["seq_cnt"], ref["seq_cnt"])
+    mag = np.add.reduceat(np.where(counted, np.abs(ref["surr"]), 0.0), cu[:-1]) if N > 0 else np.zeros(B)
+    mag = np.where(lens > 0, mag, 0.0)
+    finite_seq = np.isfinite(ref["seq_surr"])
+    serr = np.abs(got["seq_surr"].astype(np.float64) - ref["seq_surr"])[finite_seq]
+    assert (serr <= SURR_RTOL * np.maximum(mag[finite_seq], 1e-30)).all(), f"{what}: seq_surr error {serr.max():.3e}"
+    if finite_seq.all():
+        total = max(int(ref["seq_cnt"].sum()), 1)
+        assert abs(got["obj_token_mean"] - ref["obj_token_mean"]) <= SURR_RTOL * mag.sum() / total + 1e-30, what
+        per_seq_mag = np.where(ref["seq_cnt"] > 0, mag / np.maximum(ref["seq_cnt"], 1), 0.0)
+        assert abs(got["obj_seq_mean"] - ref["obj_seq_mean"]) <= SURR_RTOL * per_seq_mag.sum() / max(B, 1) + 1e-30, what
