@@ -178,6 +178,29 @@ def lmhead_logprob(hidden, weight, seq_id, step, seed, temperature, return_full=
 
 
 # --------------------------------------------------------------------------
+# Log-probability of GIVEN tokens under the current policy (Section 4, "Cross-stage
+# Importance Sampling Correction": the buffered trajectories' log-probs are
+# recomputed under pi_theta; they are L^(theta) in Eq. 8).
+# --------------------------------------------------------------------------
+def lmhead_token_logprob(hidden, weight, tokens, temperature):
+    """For every row m: z = (hidden[m] . weight[v]) / T over the vocabulary,
+    lse = logsumexp(z), logprob = z[tokens[m]] - lse.  No sampling: the token of
+    each position is given (teacher forcing).  The same temperature-scaled
+    log-softmax as `lmhead_logprob`, so that the ratio of Eq. 8 compares like
+    with like.
+
+    Returns logprob [M], lse [M] (fp64).
+    """
+    h = np.asarray(hidden, dtype=np.float64)
+    w = np.asarray(weight, dtype=np.float64)
+    tok = np.asarray(tokens, dtype=np.int64)
+    z = (h @ w.T) / float(temperature)
+    zmax = z.max(axis=1, keepdims=True)
+    lse = (zmax + np.log(np.exp(z - zmax).sum(axis=1, keepdims=True)))[:, 0]
+    return {"logprob": z[np.arange(h.shape[0]), tok] - lse, "lse": lse}
+
+
+# --------------------------------------------------------------------------
 # O3: token-level cross-stage importance ratio, clip, masked per-sequence sums
 # --------------------------------------------------------------------------
 def is_ratio(logp_cur, logp_buf, logp_roll, cu_seqlens, split, mask, eps_low, eps_high):
