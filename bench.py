@@ -40,6 +40,8 @@ def parse_args():
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 1 GiB device copy (known traffic: the scale for the "
                          "FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run)")
+    ap.add_argument("--token-logprob-m", type=int, default=8192,
+                    help="positions in the micro-batch of the given-token log-prob measurement")
     return ap.parse_args()
 
 
@@ -235,6 +237,30 @@ def main():
     result["extras"] = {"grpo_surrogate": {"call_ms": round(grpo_ms, 4), "algorithmic_bytes": ab["is"],
                                            "achieved_GBps": round(ab["is"] / (grpo_ms * 1e-3) / 1e9, 1),
                                            "workload": f"IS batch of {isb['B']} trajectories, {isb['N']} tokens"}}
+    # ---- outside the step: log-probs of given tokens under the current policy for one
+    # micro-batch of M positions (the recomputed side of the ratio), a dense contraction ----
+    if cfg.H > 0 and args.config == 2:
+        M = args.token_logprob_m
+        tb = W.make_token_logprob_inputs(cfg, M)
+        td = runner.stage_token_logprob(tb["hidden"], None, tb["tokens"], tb["temperature"], cfg.dtype, dev,
+                                        weight_dev=lm.weight)
+        for _ in range(2):
+            td.run(stream)
+        torch.cuda.synchronize()
+        reps = max(3, args.steps // 5)
+        t0e, t1e = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        t0e.record(stream)
+        for _ in range(reps):
+            td.run(stream)
+        t1e.record(stream)
+        torch.cuda.synchronize()
+        tl_ms = t0e.elapsed_time(t1e) / reps
+        flops = 2.0 * M * cfg.H * cfg.V
+        result["extras"]["token_logprob"] = {
+            "call_ms": round(tl_ms, 3), "M": M, "positions_per_s": round(M / (tl_ms * 1e-3), 1),
+            "TFLOPs": round(flops / (tl_ms * 1e-3) / 1e12, 1),
+            "mfma_frac": round(flops / (tl_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
+            "workload": f"{M} positions x LM head {cfg.H}x{cfg.V} bf16, given tokens"}
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(cfg, inp, args.cpu_sample)
     print(json.dumps(result))

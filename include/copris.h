@@ -154,6 +154,33 @@ int copris_lmhead_logprob(const void* hidden, const void* weight,
                           int C, int H, int V, int dtype, void* stream);
 
 /* ------------------------------------------------------------------------
+ * Log-probability of GIVEN tokens under the current policy (teacher forcing).
+ *
+ * Section 4, "Cross-stage Importance Sampling Correction": the log-probs of the
+ * buffered trajectories' tokens are recomputed under the current policy; they are
+ * L^(theta) in Eq. 8 (logp_cur of copris_is_ratio).  For every position m:
+ *
+ *   z[v]       = dot(hidden[m, :], weight[v, :]) / temperature
+ *   lse[m]     = log sum_v exp(z[v])
+ *   logprob[m] = z[tokens[m]] - lse[m]
+ *
+ * the same temperature-scaled log-softmax as copris_lmhead_logprob, without the
+ * sampler.  The logits are not materialised.  A token outside [0, V) gives NaN.
+ *
+ *   hidden  [M, H] dtype       weight [V, H] dtype (row v = vocabulary entry v)
+ *   tokens  [M] int32          logprob [M] fp32 out     lse [M] fp32 out or NULL
+ *   workspace  at least copris_lmhead_token_logprob_workspace_bytes() bytes, 256-byte aligned
+ *
+ * Requires temperature > 0, H % 8 == 0 for bf16 (H % 4 == 0 for fp32), V < 2^31.
+ * ------------------------------------------------------------------------ */
+size_t copris_lmhead_token_logprob_workspace_bytes(int M, int H, int V, int dtype);
+
+int copris_lmhead_token_logprob(const void* hidden, const void* weight, const int32_t* tokens,
+                                float temperature, float* logprob, float* lse,
+                                void* workspace, size_t workspace_bytes,
+                                int M, int H, int V, int dtype, void* stream);
+
+/* ------------------------------------------------------------------------
  * Token-level cross-stage importance ratio over a packed batch.
  *
  * Eq. 8: r = exp(L_cur - L_old); Eq. 3: clip(r, 1-eps_low, 1+eps_high) (Table 4

@@ -33,6 +33,9 @@ SIGNATURES = {
     "copris_lmhead_logprob_workspace_bytes": (c_size_t, [c_int] * 3),
     "copris_lmhead_logprob": (c_int, [c_void_p] * 4 + [c_uint64, c_float] + [c_void_p] * 4
                               + [c_size_t] + [c_int] * 4 + [c_void_p]),
+    "copris_lmhead_token_logprob_workspace_bytes": (c_size_t, [c_int] * 4),
+    "copris_lmhead_token_logprob": (c_int, [c_void_p] * 3 + [c_float] + [c_void_p] * 3 + [c_size_t]
+                                    + [c_int] * 4 + [c_void_p]),
     "copris_is_ratio": (c_int, [c_void_p] * 6 + [c_float, c_float] + [c_void_p] * 5
                         + [c_int, c_int64, c_void_p]),
     "copris_grpo_surrogate": (c_int, [c_void_p] * 7 + [c_float, c_float] + [c_void_p] * 5
@@ -168,3 +171,19 @@ def grpo_surrogate(logp_cur, logp_buf, logp_roll, cu_seqlens, split, mask, adv, 
         _ptr(adv), float(eps_low), float(eps_high), _ptr(surr), _ptr(grad), _ptr(seq_surr),
         _ptr(seq_cnt), _ptr(objective), B, N, _stream(stream))
     _check(code, "copris_grpo_surrogate")
+
+
+def lmhead_token_logprob_workspace_bytes(M, H, V, dtype) -> int:
+    return int(load_library().copris_lmhead_token_logprob_workspace_bytes(M, H, V, int(dtype)))
+
+
+def lmhead_token_logprob(hidden, weight, tokens, logprob, lse, workspace, *, temperature: float,
+                         dtype: int, stream=None) -> None:
+    """copris_lmhead_token_logprob on device tensors."""
+    M, H = hidden.shape
+    V = weight.shape[0]
+    code = load_library().copris_lmhead_token_logprob(
+        _ptr(hidden), _ptr(weight), _ptr(tokens), float(temperature), _ptr(logprob), _ptr(lse),
+        _ptr(workspace), workspace.numel() * workspace.element_size(), M, H, V, int(dtype),
+        _stream(stream))
+    _check(code, "copris_lmhead_token_logprob")

@@ -121,6 +121,32 @@ int copris_lmhead_logprob(const void* hidden, const void* weight, const int64_t*
                                 lse, workspace, C, H, V, dtype, static_cast<hipStream_t>(stream));
 }
 
+size_t copris_lmhead_token_logprob_workspace_bytes(int M, int H, int V, int dtype) {
+  if (M <= 0 || H <= 0 || V <= 0 || (dtype != COPRIS_F32 && dtype != COPRIS_BF16)) return 0;
+  return copris::lm_token_workspace_bytes(M, H, V, dtype);
+}
+
+int copris_lmhead_token_logprob(const void* hidden, const void* weight, const int32_t* tokens,
+                                float temperature, float* logprob, float* lse, void* workspace,
+                                size_t workspace_bytes, int M, int H, int V, int dtype,
+                                void* stream) {
+  if (!hidden || !weight || !tokens || !logprob || !workspace) return COPRIS_EINVAL;
+  if (M <= 0 || H <= 0 || V <= 0) return COPRIS_EINVAL;
+  if (!(temperature > 0.0f) || !(temperature < INFINITY)) return COPRIS_EINVAL;
+  if (dtype != COPRIS_F32 && dtype != COPRIS_BF16) return COPRIS_EUNSUPPORTED;
+  if (H % (dtype == COPRIS_BF16 ? 8 : 4) != 0) return COPRIS_EINVAL;
+  if (!aligned16(hidden) || !aligned16(weight) || !aligned16(tokens) || !aligned16(logprob) ||
+      (lse && !aligned16(lse)))
+    return COPRIS_EINVAL;
+  if (!aligned256(workspace) ||
+      workspace_bytes < copris_lmhead_token_logprob_workspace_bytes(M, H, V, dtype))
+    return COPRIS_EWORKSPACE;
+  (void)hipGetLastError();
+  return copris::launch_lmhead_token_logprob(hidden, weight, tokens, temperature, logprob, lse,
+                                             workspace, M, H, V, dtype,
+                                             static_cast<hipStream_t>(stream));
+}
+
 int copris_is_ratio(const float* logp_cur, const float* logp_buf, const float* logp_roll,
                     const int32_t* cu_seqlens, const int32_t* split, const uint8_t* mask,
                     float eps_low, float eps_high, float* ratio, float* ratio_clipped,

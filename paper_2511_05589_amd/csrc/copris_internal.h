@@ -51,6 +51,11 @@ struct LmWorkspace {
 };
 LmWorkspace lm_workspace_layout(int C, int H, int V);
 
+size_t lm_token_workspace_bytes(int M, int H, int V, int dtype);
+int launch_lmhead_token_logprob(const void* hidden, const void* weight, const int32_t* tokens,
+                                float temperature, float* logprob, float* lse, void* workspace,
+                                int M, int H, int V, int dtype, hipStream_t stream);
+
 int launch_lmhead_logprob(const void* hidden, const void* weight, const int64_t* seq_id,
                           const int32_t* step, uint64_t seed, float temperature, int32_t* token,
                           float* logprob, float* lse, void* workspace, int C, int H, int V,

@@ -115,11 +115,14 @@ template <> struct WVec<uint16_t> {
   static __device__ __forceinline__ float one(const uint16_t* p) { return bf16_to_f32(*p); }
 };
 
-template <typename T>
+// GIVEN: no sampling; the partial that holds vocabulary entry target[c] carries its logit
+// (best = +inf marks it, so the same combine picks it up).
+template <typename T, bool GIVEN>
 __global__ __launch_bounds__(256) void lmhead_generic_kernel(
     const T* __restrict__ hidden, const T* __restrict__ weight, const int64_t* __restrict__ seq_id,
-    const int32_t* __restrict__ step, uint32_t key0, uint32_t key1, float inv_temperature,
-    LmPartial* __restrict__ part, int C, int H, int V, int n_tiles) {
+    const int32_t* __restrict__ step, const int32_t* __restrict__ target, uint32_t key0,
+    uint32_t key1, float inv_temperature, LmPartial* __restrict__ part, int C, int H, int V,
+    int n_tiles) {
   constexpr int NV = WVec<T>::N;
   __shared__ float s_h[kLmTileC][kLmBK];
   const int tile = blockIdx.x, cb = blockIdx.y;
@@ -156,7 +159,15 @@ __global__ __launch_bounds__(256) void lmhead_generic_kernel(
     const int c = cb * kLmTileC + 4 * wave + r;
     if (c >= C) continue;   // uniform across the wave
     LmPartial p = empty_partial();
-    if (v_ok) {
+    if (v_ok && GIVEN) {
+      const float z = acc[r] * inv_temperature;
+      const bool hit = v == target[c];
+      p.m = z;
+      p.s = 1.0f;
+      p.z = z;
+      p.best = hit ? INFINITY : -INFINITY;
+      p.idx = hit ? v : 0x7fffffff;
+    } else if (v_ok) {
       const uint64_t sid = static_cast<uint64_t>(seq_id[c]);
       const Philox4 x = philox4x32_10(static_cast<uint32_t>(v) >> 2, static_cast<uint32_t>(step[c]),
                                       static_cast<uint32_t>(sid), static_cast<uint32_t>(sid >> 32),
@@ -255,6 +266,36 @@ __device__ __forceinline__ void lm_epilogue_block(const f32x16& acc, LmLaneState
   }
 }
 
+// Same block, no sampling: running log-sum-exp, and the logit of vocabulary entry `target`
+// if this lane holds it.
+__device__ __forceinline__ void lm_given_block(const f32x16& acc, LmLaneState& st, int vbase, int V,
+                                               bool tail, float inv_temperature, int target) {
+  float z[16];
+  float gm = -INFINITY;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) {
+    z[r] = acc[r] * inv_temperature;
+    if (tail && vbase + 8 * (r >> 2) + (r & 3) >= V) z[r] = -INFINITY;
+    gm = fmaxf(gm, z[r]);
+  }
+  const float m_new = fmaxf(st.m, gm);
+  if (m_new == -INFINITY) return;
+  st.s *= __expf(st.m - m_new);
+  st.m = m_new;
+  float s = 0.0f;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) s += __expf(z[r] - m_new);
+  st.s += s;
+  const int d = target - vbase;                  // entry vbase + 8q + j sits in accumulator 4q + j
+  if (d >= 0 && d < 32 && (d & 4) == 0 && target < V) {
+    const int sel = (d >> 3) * 4 + (d & 3);
+#pragma unroll
+    for (int r = 0; r < 16; ++r)
+      if (r == sel) st.z_best = z[r];
+    st.idx = target;
+  }
+}
+
 // ---- memory pipeline of the matrix-core kernel --------------------------------
 // Both operands reach LDS through LDS-direct loads (global_load_lds_dwordx4: each
 // lane's 16 bytes land at base + 16*lane, no registers in between), so the data in
@@ -295,11 +336,12 @@ __device__ __forceinline__ void lds_wait_all(u32x4 (&a)[4][2]) {
                  "+v"(a[2][1]), "+v"(a[3][0]), "+v"(a[3][1])::"memory");
 }
 
+template <bool GIVEN>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void lmhead_mfma_kernel(
     const uint16_t* __restrict__ hidden, const uint16_t* __restrict__ weight,
-    const int64_t* __restrict__ seq_id, const int32_t* __restrict__ step, uint32_t key0,
-    uint32_t key1, float inv_temperature, LmPartial* __restrict__ part, int C, int H, int V,
-    int n_tiles, int n_parts) {
+    const int64_t* __restrict__ seq_id, const int32_t* __restrict__ step,
+    const int32_t* __restrict__ target, uint32_t key0, uint32_t key1, float inv_temperature,
+    LmPartial* __restrict__ part, int C, int H, int V, int n_tiles, int n_parts) {
   __shared__ __attribute__((aligned(1024))) char smem[kMfLds];
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -382,10 +424,15 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   for (int i = 0; i < 4; ++i) {
     st[i] = LmLaneState{-INFINITY, 0.0f, INFINITY, 0.0f, 0.0f, 0x7fffffff};
     const int c = c0 + 128 * (i >> 1) + 64 * wq + 32 * (i & 1) + l32;
-    const uint64_t sid = c < C ? static_cast<uint64_t>(seq_id[c]) : 0;
-    step_c[i] = c < C ? static_cast<uint32_t>(step[c]) : 0;
-    sid_lo[i] = static_cast<uint32_t>(sid);
-    sid_hi[i] = static_cast<uint32_t>(sid >> 32);
+    if (GIVEN) {   // step_c holds the row's given token
+      step_c[i] = c < C ? static_cast<uint32_t>(target[c]) : 0xffffffffu;
+      sid_lo[i] = sid_hi[i] = 0;
+    } else {
+      const uint64_t sid = c < C ? static_cast<uint64_t>(seq_id[c]) : 0;
+      step_c[i] = c < C ? static_cast<uint32_t>(step[c]) : 0;
+      sid_lo[i] = static_cast<uint32_t>(sid);
+      sid_hi[i] = static_cast<uint32_t>(sid >> 32);
+    }
   }
 
   int d_idx = 0, ring = 0, hring = 0;          // W slab being consumed (flat index), W / hidden ring slots
@@ -467,7 +514,12 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     auto epilogue = [&](auto ic) __attribute__((always_inline)) {
       constexpr int i = decltype(ic)::value;       // state index = 2*half + nt
       const int c = c0 + 128 * (i >> 1) + 64 * wq + 32 * (i & 1) + l32;
-      if (c < C) {
+      if (c < C && GIVEN) {
+        lm_given_block(acc[i >> 1][0][i & 1], st[i], v0 + 64 * wm + 4 * kb, V, tail, inv_temperature,
+                       static_cast<int>(step_c[i]));
+        lm_given_block(acc[i >> 1][1][i & 1], st[i], v0 + 64 * wm + 32 + 4 * kb, V, tail,
+                       inv_temperature, static_cast<int>(step_c[i]));
+      } else if (c < C) {
         lm_epilogue_block(acc[i >> 1][0][i & 1], st[i], v0 + 64 * wm + 4 * kb, V, tail,
                           inv_temperature, step_c[i], sid_lo[i], sid_hi[i], key0, key1);
         lm_epilogue_block(acc[i >> 1][1][i & 1], st[i], v0 + 64 * wm + 32 + 4 * kb, V, tail,
@@ -492,7 +544,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     p.z = st[i].z_best;
     p.idx = st[i].idx;
     // perturbed score z + G with G = -ln(E), E = -ln u = e_best * ln 2
-    p.best = st[i].idx == 0x7fffffff ? -INFINITY : st[i].z_best - logf(st[i].e_best * kLn2f);
+    if (GIVEN) {
+      p.best = st[i].idx == 0x7fffffff ? -INFINITY : INFINITY;
+    } else {
+      p.best = st[i].idx == 0x7fffffff ? -INFINITY : st[i].z_best - logf(st[i].e_best * kLn2f);
+    }
     LmPartial o;
     o.m = __shfl_xor(p.m, 32, kWave);
     o.s = __shfl_xor(p.s, 32, kWave);
@@ -530,44 +586,73 @@ __global__ __launch_bounds__(256) void lmhead_merge_kernel(const LmPartial* __re
 #pragma unroll
     for (int w = 1; w < 256 / kWave; ++w) combine(a, s_part[w]);
     const float l = a.m + logf(a.s);
-    token[c] = a.idx;
-    logprob[c] = a.z - l;
+    if (token != nullptr) token[c] = a.idx;
+    // no candidate at all (a given token outside [0, V)): not a number
+    logprob[c] = a.idx == 0x7fffffff ? __int_as_float(0x7fc00000) : a.z - l;
     if (lse != nullptr) lse[c] = l;
   }
 }
 
-int launch_lmhead_logprob(const void* hidden, const void* weight, const int64_t* seq_id,
-                          const int32_t* step, uint64_t seed, float temperature, int32_t* token,
-                          float* logprob, float* lse, void* workspace, int C, int H, int V,
-                          int dtype, hipStream_t stream) {
-  const LmWorkspace w = lm_workspace_layout(C, H, V);
-  LmPartial* part = reinterpret_cast<LmPartial*>(static_cast<char*>(workspace) + w.part);
+// True if the matrix-core kernel takes the shape (it addresses both operands with 32-bit
+// byte offsets).
+static bool lm_use_mfma(int C, int H, int V, int dtype) {
+  return dtype == 1 && H % kMfBK == 0 && static_cast<uint64_t>(V) * H * 2 < (1ull << 32) &&
+         static_cast<uint64_t>(C) * H * 2 < (1ull << 32);
+}
+
+// Partials per row.  Matrix-core kernel: the grid is (parts, blocks of 256 rows) with
+// parts * blocks <= 512 resident workgroups where possible, so that the workgroups that
+// run at the same time walk the same vocabulary tiles (W comes from HBM once and is shared
+// through the caches) and each keeps its rows' state across all of its tiles.
+static int lm_parts(int C, int H, int V, int dtype) {
+  if (!lm_use_mfma(C, H, V, dtype)) return (V + kLmTileV - 1) / kLmTileV;
+  const int n_tiles = (V + kMfBM - 1) / kMfBM;
+  const int blocks = (C + kMfBN - 1) / kMfBN;
+  int parts = kMfMaxGrid / blocks;
+  parts = parts < 1 ? 1 : parts;
+  return parts < n_tiles ? parts : n_tiles;
+}
+
+size_t lm_token_workspace_bytes(int M, int H, int V, int dtype) {
+  return align256(static_cast<size_t>(M) * lm_parts(M, H, V, dtype) * sizeof(LmPartial));
+}
+
+// Both modes: target == nullptr samples (seq_id / step / seed), else scores the given tokens.
+static int launch_lmhead(const void* hidden, const void* weight, const int64_t* seq_id,
+                         const int32_t* step, const int32_t* target, uint64_t seed,
+                         float temperature, int32_t* token, float* logprob, float* lse,
+                         void* workspace, int C, int H, int V, int dtype, hipStream_t stream) {
+  LmPartial* part = static_cast<LmPartial*>(workspace);
   const uint32_t key0 = static_cast<uint32_t>(seed), key1 = static_cast<uint32_t>(seed >> 32);
   const float inv_t = 1.0f / temperature;
-  int n_parts = w.n_tiles;
-  // the matrix-core kernel addresses W with 32-bit byte offsets
-  if (dtype == 1 && H % kMfBK == 0 && static_cast<uint64_t>(V) * H * 2 < (1ull << 32) &&
-      static_cast<uint64_t>(C) * H * 2 < (1ull << 32)) {
+  const int n_parts = lm_parts(C, H, V, dtype);
+  const bool given = target != nullptr;
+  if (lm_use_mfma(C, H, V, dtype)) {
     const int n_tiles = (V + kMfBM - 1) / kMfBM;
-    n_parts = n_tiles < kMfMaxGrid ? n_tiles : kMfMaxGrid;   // <= w.n_tiles: fits the workspace
     const dim3 grid(n_parts, (C + kMfBN - 1) / kMfBN);
     COPRIS_PRE("lmhead_mfma_kernel");
-    hipLaunchKernelGGL(lmhead_mfma_kernel, grid, dim3(256), 0, stream,
-                       static_cast<const uint16_t*>(hidden), static_cast<const uint16_t*>(weight),
-                       seq_id, step, key0, key1, inv_t, part, C, H, V, n_tiles, n_parts);
+    if (given) {
+      hipLaunchKernelGGL(lmhead_mfma_kernel<true>, grid, dim3(256), 0, stream,
+                         static_cast<const uint16_t*>(hidden), static_cast<const uint16_t*>(weight),
+                         seq_id, step, target, key0, key1, inv_t, part, C, H, V, n_tiles, n_parts);
+    } else {
+      hipLaunchKernelGGL(lmhead_mfma_kernel<false>, grid, dim3(256), 0, stream,
+                         static_cast<const uint16_t*>(hidden), static_cast<const uint16_t*>(weight),
+                         seq_id, step, target, key0, key1, inv_t, part, C, H, V, n_tiles, n_parts);
+    }
     COPRIS_POST("lmhead_mfma_kernel");
   } else {
-    const dim3 grid(w.n_tiles, (C + kLmTileC - 1) / kLmTileC);
+    const dim3 grid(n_parts, (C + kLmTileC - 1) / kLmTileC);
+#define COPRIS_LM_GENERIC(T, G)                                                                   \
+  hipLaunchKernelGGL((lmhead_generic_kernel<T, G>), grid, dim3(256), 0, stream,                   \
+                     static_cast<const T*>(hidden), static_cast<const T*>(weight), seq_id, step,  \
+                     target, key0, key1, inv_t, part, C, H, V, n_parts)
     COPRIS_PRE("lmhead_generic_kernel");
-    if (dtype == 0) {
-      hipLaunchKernelGGL(lmhead_generic_kernel<float>, grid, dim3(256), 0, stream,
-                         static_cast<const float*>(hidden), static_cast<const float*>(weight),
-                         seq_id, step, key0, key1, inv_t, part, C, H, V, w.n_tiles);
-    } else {
-      hipLaunchKernelGGL(lmhead_generic_kernel<uint16_t>, grid, dim3(256), 0, stream,
-                         static_cast<const uint16_t*>(hidden), static_cast<const uint16_t*>(weight),
-                         seq_id, step, key0, key1, inv_t, part, C, H, V, w.n_tiles);
-    }
+    if (dtype == 0 && given) COPRIS_LM_GENERIC(float, true);
+    else if (dtype == 0) COPRIS_LM_GENERIC(float, false);
+    else if (given) COPRIS_LM_GENERIC(uint16_t, true);
+    else COPRIS_LM_GENERIC(uint16_t, false);
+#undef COPRIS_LM_GENERIC
     COPRIS_POST("lmhead_generic_kernel");
   }
   COPRIS_PRE("lmhead_merge_kernel");
@@ -575,6 +660,21 @@ int launch_lmhead_logprob(const void* hidden, const void* weight, const int64_t*
                      logprob, lse);
   COPRIS_POST("lmhead_merge_kernel");
   return 0;
+}
+
+int launch_lmhead_logprob(const void* hidden, const void* weight, const int64_t* seq_id,
+                          const int32_t* step, uint64_t seed, float temperature, int32_t* token,
+                          float* logprob, float* lse, void* workspace, int C, int H, int V,
+                          int dtype, hipStream_t stream) {
+  return launch_lmhead(hidden, weight, seq_id, step, nullptr, seed, temperature, token, logprob, lse,
+                       workspace, C, H, V, dtype, stream);
+}
+
+int launch_lmhead_token_logprob(const void* hidden, const void* weight, const int32_t* tokens,
+                                float temperature, float* logprob, float* lse, void* workspace,
+                                int M, int H, int V, int dtype, hipStream_t stream) {
+  return launch_lmhead(hidden, weight, nullptr, nullptr, tokens, 0, temperature, nullptr, logprob,
+                       lse, workspace, M, H, V, dtype, stream);
 }
 
 }  // namespace copris

@@ -224,3 +224,44 @@ def run_grpo_surrogate(b: dict, use_mask: bool = True) -> dict:
     return {"surr": d.surr.cpu().numpy()[:N], "grad": d.grad.cpu().numpy()[:N],
             "seq_surr": d.seq_surr.cpu().numpy()[:B], "seq_cnt": d.seq_cnt.cpu().numpy()[:B],
             "obj_token_mean": float(obj[0]), "obj_seq_mean": float(obj[1])}
+
+
+@dataclass
+class TokenLogprobDevice:
+    hidden: torch.Tensor
+    weight: torch.Tensor
+    tokens: torch.Tensor
+    logprob: torch.Tensor
+    lse: torch.Tensor
+    ws: torch.Tensor
+    temperature: float
+    dtype: int
+
+    def run(self, stream=None):
+        binding.lmhead_token_logprob(self.hidden, self.weight, self.tokens, self.logprob, self.lse,
+                                     self.ws, temperature=self.temperature, dtype=self.dtype,
+                                     stream=stream)
+
+
+def stage_token_logprob(hidden, weight, tokens, temperature: float, dtype: str, device=None,
+                        weight_dev: Optional[torch.Tensor] = None) -> TokenLogprobDevice:
+    """hidden / weight are storage arrays (bf16 as uint16 bit patterns); weight_dev lets a
+    caller reuse a weight tensor that is already on the device."""
+    device = device or require_gpu()
+    h = to_device(hidden, device=device)
+    w = weight_dev if weight_dev is not None else to_device(weight, device=device)
+    t = to_device(np.asarray(tokens, dtype=np.int32), device=device)
+    M, H = h.shape
+    V = w.shape[0]
+    code = dtype_code(dtype)
+    logprob = torch.full((M,), float("nan"), dtype=torch.float32, device=device)
+    lse = torch.full((M,), float("nan"), dtype=torch.float32, device=device)
+    ws = workspace(binding.lmhead_token_logprob_workspace_bytes(M, H, V, code), device)
+    return TokenLogprobDevice(h, w, t, logprob, lse, ws, float(temperature), code)
+
+
+def run_token_logprob(hidden, weight, tokens, temperature: float, dtype: str):
+    d = stage_token_logprob(hidden, weight, tokens, temperature, dtype)
+    d.run()
+    torch.cuda.synchronize()
+    return d.logprob.cpu().numpy(), d.lse.cpu().numpy()

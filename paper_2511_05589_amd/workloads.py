@@ -297,6 +297,19 @@ def make_decode_inputs(cfg: DecodeConfig, *, ctx_len: Optional[np.ndarray] = Non
     return out
 
 
+def make_token_logprob_inputs(cfg: DecodeConfig, M: int) -> dict:
+    """One micro-batch of M positions for the log-prob recompute under the current policy:
+    the LM head of `cfg` (the same weight stream as make_decode_inputs), hidden states
+    N(0,1) and given tokens uniform over the vocabulary, both from a stream of their own."""
+    st = substreams(cfg.seed)
+    rng_h, rng_t = np.random.default_rng(cfg.seed + 77).spawn(2)
+    return {"cfg": cfg, "M": int(M),
+            "hidden": _normal_storage(rng_h, (M, cfg.H), cfg.dtype),
+            "weight": _normal_storage(st["w"], (cfg.V, cfg.H), cfg.dtype, std=0.02),
+            "tokens": rng_t.integers(0, cfg.V, size=M, dtype=np.int64).astype(np.int32),
+            "temperature": float(cfg.temperature)}
+
+
 def make_small_decode_case(seed: int, C: int, Hq: int, Hkv: int, D: int, dtype: str,
                            page_size: int, ctx_len, *, spare_frac: float = 0.25,
                            max_pages: Optional[int] = None, poison: bool = True) -> dict:

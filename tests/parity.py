@@ -155,3 +155,20 @@ def check_grpo(got, ref, b, use_mask=True, what=""):
         assert abs(got["obj_token_mean"] - ref["obj_token_mean"]) <= SURR_RTOL * mag.sum() / total + 1e-30, what
         per_seq_mag = np.where(ref["seq_cnt"] > 0, mag / np.maximum(ref["seq_cnt"], 1), 0.0)
         assert abs(got["obj_seq_mean"] - ref["obj_seq_mean"]) <= SURR_RTOL * per_seq_mag.sum() / max(B, 1) + 1e-30, what
+
+
+# ---- log-prob of given tokens ------------------------------------------------
+def oracle_token_logprob(hidden, weight, tokens, temperature, dtype, rows=None):
+    h = W.to_f32(hidden, dtype)
+    t = np.asarray(tokens)
+    if rows is not None:
+        h, t = h[rows], t[rows]
+    return O.lmhead_token_logprob(h, W.to_f32(weight, dtype), t, temperature)
+
+
+def check_token_logprob(logprob, lse, ref, what=""):
+    err = np.abs(logprob.astype(np.float64) - ref["logprob"]).max()
+    assert err <= LOGPROB_TOL, f"{what}: logprob error {err:.3e}"
+    lerr = np.abs(lse.astype(np.float64) - ref["lse"]).max()
+    assert lerr <= LOGPROB_TOL, f"{what}: lse error {lerr:.3e}"
+    return err
