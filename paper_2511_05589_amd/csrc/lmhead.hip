@@ -568,6 +568,234 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 }
 
 // --------------------------------------------------------------------------
+// matrix-core kernel for micro-batches of given tokens (many row blocks).
+//
+// With hundreds of row blocks the work is a plain dense contraction and what counts is
+// bytes moved into LDS per flop.  One 8-wave workgroup per CU owns a 256 (vocab) x 256
+// (batch) tile - 64 KB of operands per 64-wide slab of the hidden dimension instead of
+// the 96 KB that two 128 x 256 workgroups move for the same flops - and the whole 160 KB
+// of LDS is one pipeline: W slabs [256][64] in a ring of three (issued three slabs ahead),
+// hidden slabs [256][64] in a ring of two.  Every wave issues its eighth of both slabs,
+// the hidden part first, so that its in-order load counter can wait for the hidden slab
+// while the younger W slab stays in flight.  The one barrier per slab sits before the last
+// eight products of the slab, after all of the slab's LDS reads: the refill and the first
+// operand reads of the next slab are issued there and overlap those products.
+// No sampler here: the epilogue is the running log-sum-exp and the given token's logit.
+// --------------------------------------------------------------------------
+constexpr int kGmBM = 256;                          // vocabulary rows per tile
+constexpr int kGmBN = 256;                          // batch rows per workgroup
+constexpr int kGmSlab = 256 * kMfBK * 2;            // 32 KB
+constexpr int kGmNW = 3;                            // W ring slabs
+constexpr int kGmHRing = kGmNW * kGmSlab;           // hidden ring (2 slabs) starts here
+constexpr int kGmLds = kGmHRing + 2 * kGmSlab;      // 160 KB
+constexpr int kGmMaxGrid = 256;                     // one workgroup per CU
+constexpr int kGmMinRows = 1024;                    // below this the 128-row kernel is used
+
+template <int N>
+__device__ __forceinline__ void lds_wait6(u32x4 (&a)[4], u32x4 (&b)[2]) {
+  asm volatile("s_waitcnt lgkmcnt(%6)"
+               : "+v"(a[0]), "+v"(a[1]), "+v"(a[2]), "+v"(a[3]), "+v"(b[0]), "+v"(b[1])
+               : "n"(N)
+               : "memory");
+}
+
+__global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) void lmhead_gemm_given_kernel(
+    const uint16_t* __restrict__ hidden, const uint16_t* __restrict__ weight,
+    const int32_t* __restrict__ target, float inv_temperature, LmPartial* __restrict__ part, int C,
+    int H, int V, int n_tiles, int n_parts) {
+  __shared__ __attribute__((aligned(1024))) char smem[kGmLds];
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm = wave >> 2, wq = wave & 3;     // 128-row vocabulary half; 64-row batch block
+  const int l32 = lane & 31, kb = lane >> 5;
+  const int c0 = blockIdx.y * kGmBN;
+  const int nkd = H / kMfBK;
+  const uint32_t lds0 = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(smem));
+  const uint32_t pitch = static_cast<uint32_t>(H) * 2u;
+
+  // operand read offsets inside a slab (bytes); each further 32-row block adds 4096
+  uint32_t a_off[4], b_off[4];
+#pragma unroll
+  for (int k16 = 0; k16 < 4; ++k16) {
+    a_off[k16] = lm_swz(128 * wm + l32, 2 * k16 + kb) * 16;
+    b_off[k16] = lm_swz(64 * wq + l32, 2 * k16 + kb) * 16;
+  }
+
+  // ---- loader cursors (wave-uniform).  Wave w moves rows 32w .. 32w+31 of every slab:
+  // four instructions of 8 rows x 128 bytes; LDS position 64*chunk + lane holds (row
+  // 8*chunk + lane/8, stored granule lane%8) and the lane fetches the global granule the
+  // swizzle maps there ((row>>1)&7 = lane>>4 for even chunks, +4 for odd ones).
+  const int my_tiles = (n_tiles - 1 - static_cast<int>(blockIdx.x)) / static_cast<int>(gridDim.x) + 1;
+  const int total = my_tiles * nkd;            // slabs this workgroup consumes
+  const int ld_row = 32 * wave + (lane >> 3);
+  const uint32_t ld_g = ((lane & 7) ^ (lane >> 4)) * 16;
+  int w_n = 0, w_tile = blockIdx.x, w_kd = 0, w_slot = 0;
+  int h_n = 0, h_kd = 0, h_slot = 0;
+  const char* wbase = reinterpret_cast<const char*>(weight);
+  const char* hbase = reinterpret_cast<const char*>(hidden);
+  auto issue_w = [&]() __attribute__((always_inline)) {
+    char* dst = smem + w_slot * kGmSlab + (4 * wave) * 1024;
+    const uint32_t koff = static_cast<uint32_t>(w_kd) * (kMfBK * 2) + ld_g;
+    const int vrow = w_tile * kGmBM + ld_row;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int v = min(vrow + 8 * j, V - 1);      // rows past V re-read the last row (masked later)
+      __builtin_amdgcn_global_load_lds(wbase + (static_cast<uint32_t>(v) * pitch + (koff ^ ((j & 1) * 64))),
+                                       dst + j * 1024, 16, 0, 0);
+    }
+    w_slot = w_slot + 1 == kGmNW ? 0 : w_slot + 1;
+    ++w_n;
+    if (++w_kd == nkd) {
+      w_kd = 0;
+      w_tile += gridDim.x;
+    }
+  };
+  auto issue_h = [&]() __attribute__((always_inline)) {
+    char* dst = smem + kGmHRing + h_slot * kGmSlab + (4 * wave) * 1024;
+    const uint32_t koff = static_cast<uint32_t>(h_kd) * (kMfBK * 2) + ld_g;
+    const int crow = c0 + ld_row;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int c = min(crow + 8 * j, C - 1);      // rows past C duplicate the last row (unused)
+      __builtin_amdgcn_global_load_lds(hbase + (static_cast<uint32_t>(c) * pitch + (koff ^ ((j & 1) * 64))),
+                                       dst + j * 1024, 16, 0, 0);
+    }
+    h_slot ^= 1;
+    ++h_n;
+    if (++h_kd == nkd) h_kd = 0;
+  };
+
+  // this lane owns batch rows c0 + 64*wq + 32*nt + l32; their given tokens are fetched
+  // before the pipeline starts (the prologue's wait covers them)
+  LmLaneState st[2];
+  int tgt[2];
+#pragma unroll
+  for (int nt = 0; nt < 2; ++nt) {
+    st[nt] = LmLaneState{-INFINITY, 0.0f, INFINITY, 0.0f, 0.0f, 0x7fffffff};
+    const int c = c0 + 64 * wq + 32 * nt + l32;
+    tgt[nt] = c < C ? target[c] : -1;
+  }
+
+  // prologue: slab 0 lands, then the steady order "hidden(d+2), W(d+3)" is set up
+  issue_h();
+  issue_w();
+  if (w_n < total) issue_w();
+  asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
+  if (h_n < total) issue_h();
+  if (w_n < total) issue_w();
+
+  u32x4 a[2][4], b[2][2];
+  int wslot = 0, hslot = 0;                     // ring slots of the slab being consumed
+  uint32_t wb = lds0, hb = lds0 + kGmHRing;
+  auto read_operands = [&](auto bufc, auto k16c) __attribute__((always_inline)) {
+    constexpr int buf = decltype(bufc)::value, k16 = decltype(k16c)::value;
+    a[buf][0] = lds_read128<0>(wb + a_off[k16]);
+    a[buf][1] = lds_read128<4096>(wb + a_off[k16]);
+    a[buf][2] = lds_read128<8192>(wb + a_off[k16]);
+    a[buf][3] = lds_read128<12288>(wb + a_off[k16]);
+    b[buf][0] = lds_read128<0>(hb + b_off[k16]);
+    b[buf][1] = lds_read128<4096>(hb + b_off[k16]);
+  };
+  using I0 = std::integral_constant<int, 0>;
+  using I1 = std::integral_constant<int, 1>;
+  using I2 = std::integral_constant<int, 2>;
+  using I3 = std::integral_constant<int, 3>;
+  read_operands(I0{}, I0{});
+
+  int d = 0;
+  for (int tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
+    const int v0 = tile * kGmBM;
+    f32x16 acc[4][2];
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i >> 1][i & 1][r] = 0.0f;
+    auto products = [&](auto bufc) __attribute__((always_inline)) {
+      constexpr int buf = decltype(bufc)::value;
+      const bf16x8 fb0 = __builtin_bit_cast(bf16x8, b[buf][0]);
+      const bf16x8 fb1 = __builtin_bit_cast(bf16x8, b[buf][1]);
+#pragma unroll
+      for (int rb = 0; rb < 4; ++rb) {
+        const bf16x8 fa = __builtin_bit_cast(bf16x8, a[buf][rb]);
+        acc[rb][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa, fb0, acc[rb][0], 0, 0, 0);
+        acc[rb][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa, fb1, acc[rb][1], 0, 0, 0);
+      }
+    };
+
+    for (int kd = 0; kd < nkd; ++kd, ++d) {
+      read_operands(I1{}, I1{});
+      lds_wait6<6>(a[0], b[0]);
+      products(I0{});
+      read_operands(I0{}, I2{});
+      lds_wait6<6>(a[1], b[1]);
+      products(I1{});
+      read_operands(I1{}, I3{});
+      lds_wait6<6>(a[0], b[0]);
+      products(I0{});
+      lds_wait6<0>(a[1], b[1]);                 // every LDS read of slab d is complete
+      if (d + 1 < total) {
+        // slab d+1 has landed (this wave's part: hidden(d+1) is older than W(d+2)) ...
+        if (d + 2 < total) {
+          asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+        } else {
+          asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        }
+        asm volatile("s_barrier" ::: "memory");   // ... for every wave, and all are done reading slab d
+        if (h_n < total) issue_h();               // hidden(d+2) into the slot of slab d
+        if (w_n < total) issue_w();               // W(d+3) into the slot of slab d
+        wslot = wslot + 1 == kGmNW ? 0 : wslot + 1;
+        hslot ^= 1;
+        wb = lds0 + wslot * kGmSlab;
+        hb = lds0 + kGmHRing + hslot * kGmSlab;
+        read_operands(I0{}, I0{});                // first operands of slab d+1, under the products below
+      }
+      products(I1{});
+    }
+
+    const bool tail = v0 + kGmBM > V;   // only the last tile can hold rows past V
+#pragma unroll
+    for (int nt = 0; nt < 2; ++nt) {
+      const int c = c0 + 64 * wq + 32 * nt + l32;
+      if (c < C) {
+#pragma unroll
+        for (int rb = 0; rb < 4; ++rb)
+          lm_given_block(acc[rb][nt], st[nt], v0 + 128 * wm + 32 * rb + 4 * kb, V, tail, inv_temperature,
+                         tgt[nt]);
+      }
+    }
+  }
+
+  // lane state -> partial; combine the two k-halves of a wave, then the two vocabulary
+  // halves.  The exchange buffer reuses the ring memory: all slabs have been consumed.
+  asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+  LmPartial(*s_part)[64] = reinterpret_cast<LmPartial(*)[64]>(smem);
+#pragma unroll
+  for (int nt = 0; nt < 2; ++nt) {
+    LmPartial p;
+    p.m = st[nt].m;
+    p.s = st[nt].s;
+    p.z = st[nt].z_best;
+    p.idx = st[nt].idx;
+    p.best = st[nt].idx == 0x7fffffff ? -INFINITY : INFINITY;
+    LmPartial o;
+    o.m = __shfl_xor(p.m, 32, kWave);
+    o.s = __shfl_xor(p.s, 32, kWave);
+    o.best = __shfl_xor(p.best, 32, kWave);
+    o.z = __shfl_xor(p.z, 32, kWave);
+    o.idx = __shfl_xor(p.idx, 32, kWave);
+    combine(p, o);
+    if (wm == 1 && kb == 0) s_part[wq][32 * nt + l32] = p;
+    __syncthreads();
+    if (wm == 0 && kb == 0) {
+      combine(p, s_part[wq][32 * nt + l32]);
+      const int c = c0 + 64 * wq + 32 * nt + l32;
+      if (c < C) part[static_cast<size_t>(c) * n_parts + blockIdx.x] = p;
+    }
+    __syncthreads();
+  }
+}
+
+// --------------------------------------------------------------------------
 // merge: one workgroup per batch row over its partials.
 // --------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void lmhead_merge_kernel(const LmPartial* __restrict__ part,
@@ -593,28 +821,35 @@ __global__ __launch_bounds__(256) void lmhead_merge_kernel(const LmPartial* __re
   }
 }
 
-// True if the matrix-core kernel takes the shape (it addresses both operands with 32-bit
+// True if the matrix-core kernels take the shape (they address both operands with 32-bit
 // byte offsets).
 static bool lm_use_mfma(int C, int H, int V, int dtype) {
   return dtype == 1 && H % kMfBK == 0 && static_cast<uint64_t>(V) * H * 2 < (1ull << 32) &&
          static_cast<uint64_t>(C) * H * 2 < (1ull << 32);
 }
+// Micro-batches of given tokens go to the 256 x 256 kernel.
+static bool lm_use_gemm(int C, int H, int V, int dtype, bool given) {
+  return given && C >= kGmMinRows && lm_use_mfma(C, H, V, dtype);
+}
 
-// Partials per row.  Matrix-core kernel: the grid is (parts, blocks of 256 rows) with
-// parts * blocks <= 512 resident workgroups where possible, so that the workgroups that
-// run at the same time walk the same vocabulary tiles (W comes from HBM once and is shared
-// through the caches) and each keeps its rows' state across all of its tiles.
-static int lm_parts(int C, int H, int V, int dtype) {
+// Partials per row.  Matrix-core kernels: the grid is (parts, blocks of 256 rows) with
+// parts * blocks <= the resident workgroups (512, or 256 for the 256 x 256 kernel) where
+// possible, so that the workgroups that run at the same time walk the same vocabulary tiles
+// (W comes from HBM once and is shared through the caches) and each keeps its rows' state
+// across all of its tiles.
+static int lm_parts(int C, int H, int V, int dtype, bool given) {
   if (!lm_use_mfma(C, H, V, dtype)) return (V + kLmTileV - 1) / kLmTileV;
-  const int n_tiles = (V + kMfBM - 1) / kMfBM;
+  const bool gemm = lm_use_gemm(C, H, V, dtype, given);
+  const int bm = gemm ? kGmBM : kMfBM;
+  const int n_tiles = (V + bm - 1) / bm;
   const int blocks = (C + kMfBN - 1) / kMfBN;
-  int parts = kMfMaxGrid / blocks;
+  int parts = (gemm ? kGmMaxGrid : kMfMaxGrid) / blocks;
   parts = parts < 1 ? 1 : parts;
   return parts < n_tiles ? parts : n_tiles;
 }
 
 size_t lm_token_workspace_bytes(int M, int H, int V, int dtype) {
-  return align256(static_cast<size_t>(M) * lm_parts(M, H, V, dtype) * sizeof(LmPartial));
+  return align256(static_cast<size_t>(M) * lm_parts(M, H, V, dtype, true) * sizeof(LmPartial));
 }
 
 // Both modes: target == nullptr samples (seq_id / step / seed), else scores the given tokens.
@@ -625,9 +860,17 @@ static int launch_lmhead(const void* hidden, const void* weight, const int64_t* 
   LmPartial* part = static_cast<LmPartial*>(workspace);
   const uint32_t key0 = static_cast<uint32_t>(seed), key1 = static_cast<uint32_t>(seed >> 32);
   const float inv_t = 1.0f / temperature;
-  const int n_parts = lm_parts(C, H, V, dtype);
   const bool given = target != nullptr;
-  if (lm_use_mfma(C, H, V, dtype)) {
+  const int n_parts = lm_parts(C, H, V, dtype, given);
+  if (lm_use_gemm(C, H, V, dtype, given)) {
+    const int n_tiles = (V + kGmBM - 1) / kGmBM;
+    const dim3 grid(n_parts, (C + kGmBN - 1) / kGmBN);
+    COPRIS_PRE("lmhead_gemm_given_kernel");
+    hipLaunchKernelGGL(lmhead_gemm_given_kernel, grid, dim3(512), 0, stream,
+                       static_cast<const uint16_t*>(hidden), static_cast<const uint16_t*>(weight),
+                       target, inv_t, part, C, H, V, n_tiles, n_parts);
+    COPRIS_POST("lmhead_gemm_given_kernel");
+  } else if (lm_use_mfma(C, H, V, dtype)) {
     const int n_tiles = (V + kMfBM - 1) / kMfBM;
     const dim3 grid(n_parts, (C + kMfBN - 1) / kMfBN);
     COPRIS_PRE("lmhead_mfma_kernel");

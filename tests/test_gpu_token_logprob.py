@@ -31,6 +31,8 @@ def _case(seed, M, H, V, dtype, w_std=0.05):
 @pytest.mark.parametrize("dtype", [W.F32, W.BF16])
 @pytest.mark.parametrize("M,H,V", [(1, 64, 50), (17, 512, 4099), (256, 128, 2500), (300, 512, 3001),
                                    (1000, 256, 9000),     # four row blocks share the persistent grid
+                                   (1300, 256, 9001),     # the 256 x 256 kernel: six row blocks, ragged tails
+                                   (2049, 128, 700),      # ... fewer tiles than workgroups, one-row last block
                                    (129, 192, 70000),     # more tiles than workgroups per row block
                                    (40, 3584, 777), (5, 72, 260)])
 def test_small_shapes(R, dtype, M, H, V):
