@@ -608,7 +608,10 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = wave >> 2, wq = wave & 3;     // 128-row vocabulary half; 64-row batch block
   const int l32 = lane & 31, kb = lane >> 5;
-  const int c0 = blockIdx.y * kGmBN;
+  // grid = (row blocks, tile lanes): consecutive workgroups (which the dispatcher deals out
+  // to the XCDs in turn) differ in the row block, so one XCD's L2 sees few row blocks
+  const int lane_id = blockIdx.y, n_lanes = gridDim.y;
+  const int c0 = blockIdx.x * kGmBN;
   const int nkd = H / kMfBK;
   const uint32_t lds0 = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(smem));
   const uint32_t pitch = static_cast<uint32_t>(H) * 2u;
@@ -625,11 +628,11 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   // four instructions of 8 rows x 128 bytes; LDS position 64*chunk + lane holds (row
   // 8*chunk + lane/8, stored granule lane%8) and the lane fetches the global granule the
   // swizzle maps there ((row>>1)&7 = lane>>4 for even chunks, +4 for odd ones).
-  const int my_tiles = (n_tiles - 1 - static_cast<int>(blockIdx.x)) / static_cast<int>(gridDim.x) + 1;
+  const int my_tiles = (n_tiles - 1 - lane_id) / n_lanes + 1;
   const int total = my_tiles * nkd;            // slabs this workgroup consumes
   const int ld_row = 32 * wave + (lane >> 3);
   const uint32_t ld_g = ((lane & 7) ^ (lane >> 4)) * 16;
-  int w_n = 0, w_tile = blockIdx.x, w_kd = 0, w_slot = 0;
+  int w_n = 0, w_tile = lane_id, w_kd = 0, w_slot = 0;
   int h_n = 0, h_kd = 0, h_slot = 0;
   const char* wbase = reinterpret_cast<const char*>(weight);
   const char* hbase = reinterpret_cast<const char*>(hidden);
@@ -647,7 +650,7 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     ++w_n;
     if (++w_kd == nkd) {
       w_kd = 0;
-      w_tile += gridDim.x;
+      w_tile += n_lanes;
     }
   };
   auto issue_h = [&]() __attribute__((always_inline)) {
@@ -703,7 +706,7 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   read_operands(I0{}, I0{});
 
   int d = 0;
-  for (int tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
+  for (int tile = lane_id; tile < n_tiles; tile += n_lanes) {
     const int v0 = tile * kGmBM;
     f32x16 acc[4][2];
 #pragma unroll
@@ -789,7 +792,7 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     if (wm == 0 && kb == 0) {
       combine(p, s_part[wq][32 * nt + l32]);
       const int c = c0 + 64 * wq + 32 * nt + l32;
-      if (c < C) part[static_cast<size_t>(c) * n_parts + blockIdx.x] = p;
+      if (c < C) part[static_cast<size_t>(c) * n_parts + lane_id] = p;
     }
     __syncthreads();
   }
@@ -864,7 +867,7 @@ static int launch_lmhead(const void* hidden, const void* weight, const int64_t* 
   const int n_parts = lm_parts(C, H, V, dtype, given);
   if (lm_use_gemm(C, H, V, dtype, given)) {
     const int n_tiles = (V + kGmBM - 1) / kGmBM;
-    const dim3 grid(n_parts, (C + kGmBN - 1) / kGmBN);
+    const dim3 grid((C + kGmBN - 1) / kGmBN, n_parts);
     COPRIS_PRE("lmhead_gemm_given_kernel");
     hipLaunchKernelGGL(lmhead_gemm_given_kernel, grid, dim3(512), 0, stream,
                        static_cast<const uint16_t*>(hidden), static_cast<const uint16_t*>(weight),
