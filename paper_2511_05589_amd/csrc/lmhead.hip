@@ -589,7 +589,7 @@ constexpr int kGmNW = 3;                            // W ring slabs
 constexpr int kGmHRing = kGmNW * kGmSlab;           // hidden ring (2 slabs) starts here
 constexpr int kGmLds = kGmHRing + 2 * kGmSlab;      // 160 KB
 constexpr int kGmMaxGrid = 256;                     // one workgroup per CU
-constexpr int kGmMinRows = 1024;                    // below this the 128-row kernel is used
+constexpr int kGmMinRows = 384;                     // below this the 128-row kernel is used
 
 template <int N>
 __device__ __forceinline__ void lds_wait6(u32x4 (&a)[4], u32x4 (&b)[2]) {
@@ -599,6 +599,7 @@ __device__ __forceinline__ void lds_wait6(u32x4 (&a)[4], u32x4 (&b)[2]) {
                : "memory");
 }
 
+template <bool W_DEEP>
 __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) void lmhead_gemm_given_kernel(
     const uint16_t* __restrict__ hidden, const uint16_t* __restrict__ weight,
     const int32_t* __restrict__ target, float inv_temperature, LmPartial* __restrict__ part, int C,
@@ -615,6 +616,9 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   const int nkd = H / kMfBK;
   const uint32_t lds0 = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(smem));
   const uint32_t pitch = static_cast<uint32_t>(H) * 2u;
+  // the deep stream (three slots, issued three slabs ahead) and the shallow one (two slots)
+  constexpr int kWSlots = W_DEEP ? 3 : 2, kHSlots = W_DEEP ? 2 : 3;
+  constexpr int kHBase = kWSlots * kGmSlab;
 
   // operand read offsets inside a slab (bytes); each further 32-row block adds 4096
   uint32_t a_off[4], b_off[4];
@@ -646,7 +650,7 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
       __builtin_amdgcn_global_load_lds(wbase + (static_cast<uint32_t>(v) * pitch + (koff ^ ((j & 1) * 64))),
                                        dst + j * 1024, 16, 0, 0);
     }
-    w_slot = w_slot + 1 == kGmNW ? 0 : w_slot + 1;
+    w_slot = w_slot + 1 == kWSlots ? 0 : w_slot + 1;
     ++w_n;
     if (++w_kd == nkd) {
       w_kd = 0;
@@ -654,7 +658,7 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     }
   };
   auto issue_h = [&]() __attribute__((always_inline)) {
-    char* dst = smem + kGmHRing + h_slot * kGmSlab + (4 * wave) * 1024;
+    char* dst = smem + kHBase + h_slot * kGmSlab + (4 * wave) * 1024;
     const uint32_t koff = static_cast<uint32_t>(h_kd) * (kMfBK * 2) + ld_g;
     const int crow = c0 + ld_row;
 #pragma unroll
@@ -663,7 +667,7 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
       __builtin_amdgcn_global_load_lds(hbase + (static_cast<uint32_t>(c) * pitch + (koff ^ ((j & 1) * 64))),
                                        dst + j * 1024, 16, 0, 0);
     }
-    h_slot ^= 1;
+    h_slot = h_slot + 1 == kHSlots ? 0 : h_slot + 1;
     ++h_n;
     if (++h_kd == nkd) h_kd = 0;
   };
@@ -680,16 +684,22 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   }
 
   // prologue: slab 0 lands, then the steady order "hidden(d+2), W(d+3)" is set up
-  issue_h();
-  issue_w();
-  if (w_n < total) issue_w();
+  auto issue_shallow = [&]() __attribute__((always_inline)) {
+    if (W_DEEP) { if (h_n < total) issue_h(); } else { if (w_n < total) issue_w(); }
+  };
+  auto issue_deep = [&]() __attribute__((always_inline)) {
+    if (W_DEEP) { if (w_n < total) issue_w(); } else { if (h_n < total) issue_h(); }
+  };
+  issue_shallow();
+  issue_deep();
+  issue_deep();
   asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
-  if (h_n < total) issue_h();
-  if (w_n < total) issue_w();
+  issue_shallow();
+  issue_deep();
 
   u32x4 a[2][4], b[2][2];
   int wslot = 0, hslot = 0;                     // ring slots of the slab being consumed
-  uint32_t wb = lds0, hb = lds0 + kGmHRing;
+  uint32_t wb = lds0, hb = lds0 + kHBase;
   auto read_operands = [&](auto bufc, auto k16c) __attribute__((always_inline)) {
     constexpr int buf = decltype(bufc)::value, k16 = decltype(k16c)::value;
     a[buf][0] = lds_read128<0>(wb + a_off[k16]);
@@ -737,19 +747,19 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
       products(I0{});
       lds_wait6<0>(a[1], b[1]);                 // every LDS read of slab d is complete
       if (d + 1 < total) {
-        // slab d+1 has landed (this wave's part: hidden(d+1) is older than W(d+2)) ...
+        // slab d+1 has landed (this wave's part: only the deep stream's slab d+2 is younger) ...
         if (d + 2 < total) {
           asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
         } else {
           asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         }
         asm volatile("s_barrier" ::: "memory");   // ... for every wave, and all are done reading slab d
-        if (h_n < total) issue_h();               // hidden(d+2) into the slot of slab d
-        if (w_n < total) issue_w();               // W(d+3) into the slot of slab d
-        wslot = wslot + 1 == kGmNW ? 0 : wslot + 1;
-        hslot ^= 1;
+        issue_shallow();                          // slab d+2 of the shallow stream, into the slot of slab d
+        issue_deep();                             // slab d+3 of the deep stream, likewise
+        wslot = wslot + 1 == kWSlots ? 0 : wslot + 1;
+        hslot = hslot + 1 == kHSlots ? 0 : hslot + 1;
         wb = lds0 + wslot * kGmSlab;
-        hb = lds0 + kGmHRing + hslot * kGmSlab;
+        hb = lds0 + kHBase + hslot * kGmSlab;
         read_operands(I0{}, I0{});                // first operands of slab d+1, under the products below
       }
       products(I1{});
@@ -869,7 +879,7 @@ static int launch_lmhead(const void* hidden, const void* weight, const int64_t* 
     const int n_tiles = (V + kGmBM - 1) / kGmBM;
     const dim3 grid((C + kGmBN - 1) / kGmBN, n_parts);
     COPRIS_PRE("lmhead_gemm_given_kernel");
-    hipLaunchKernelGGL(lmhead_gemm_given_kernel, grid, dim3(512), 0, stream,
+    hipLaunchKernelGGL(lmhead_gemm_given_kernel<true>, grid, dim3(512), 0, stream,
                        static_cast<const uint16_t*>(hidden), static_cast<const uint16_t*>(weight),
                        target, inv_t, part, C, H, V, n_tiles, n_parts);
     COPRIS_POST("lmhead_gemm_given_kernel");
