@@ -133,6 +133,61 @@ def decode_attn(q, k_cache, v_cache, block_table, ctx_len, scale, page_size=None
 
 
 # --------------------------------------------------------------------------
+# Re-prefill of resumed partial trajectories (Section 4, "Prioritized Resumption";
+# Section 5.3 names the re-prefilling of off-policy trajectories as a cost): the
+# buffered prefix of a trajectory is run through the model again under the new
+# weights, which refills its KV pages.  The attention part of that: causal
+# self-attention over packed variable-length sequences, and the page fill.
+# --------------------------------------------------------------------------
+def prefill_attn(q, k, v, cu_seqlens, scale):
+    """Causal softmax attention over a packed batch of sequences.
+
+    q [T, Hq, D], k, v [T, Hkv, D]; sequence b owns rows cu_seqlens[b] ..
+    cu_seqlens[b+1]-1 in token order.  Query head h reads KV head h // (Hq // Hkv).
+    Token t of a sequence attends to tokens 0..t of the same sequence:
+    out[t] = softmax_{u<=t}(scale * q[t].k[u]) . v[u].
+    Returns (out [T, Hq, D] fp64, lse [T, Hq] fp64).
+    """
+    q = np.asarray(q, dtype=np.float64)
+    k = np.asarray(k, dtype=np.float64)
+    v = np.asarray(v, dtype=np.float64)
+    T, Hq, D = q.shape
+    Hkv = k.shape[1]
+    assert Hq % Hkv == 0
+    g = Hq // Hkv
+    cu = np.asarray(cu_seqlens, dtype=np.int64)
+    out = np.zeros((T, Hq, D))
+    lse = np.full((T, Hq), -np.inf)
+    for b in range(cu.size - 1):
+        s0, s1 = int(cu[b]), int(cu[b + 1])
+        for t in range(s0, s1):
+            for h in range(Hq):
+                K = k[s0:t + 1, h // g]
+                V = v[s0:t + 1, h // g]
+                s = scale * (K @ q[t, h])
+                m = s.max()
+                p = np.exp(s - m)
+                denom = p.sum()
+                out[t, h] = (p @ V) / denom
+                lse[t, h] = m + np.log(denom)
+    return out, lse
+
+
+def kv_page_fill(k, v, cu_seqlens, block_table, k_cache, v_cache):
+    """Writes every sequence's K and V rows into its pages (in place): token t of
+    sequence b goes to page block_table[b, t // P], slot t % P.  Slots that no token
+    maps to are left as they were.  Pure data movement, in the caches' own dtype."""
+    cu = np.asarray(cu_seqlens, dtype=np.int64)
+    P = k_cache.shape[2]
+    for b in range(cu.size - 1):
+        s0, s1 = int(cu[b]), int(cu[b + 1])
+        for t in range(s1 - s0):
+            page = int(block_table[b, t // P])
+            k_cache[page, :, t % P, :] = k[s0 + t]
+            v_cache[page, :, t % P, :] = v[s0 + t]
+
+
+# --------------------------------------------------------------------------
 # O2: LM head + log-softmax + Gumbel-max sample + chosen-token log-prob
 # --------------------------------------------------------------------------
 def lmhead_logprob(hidden, weight, seq_id, step, seed, temperature, return_full=False):

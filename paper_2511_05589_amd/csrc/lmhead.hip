@@ -745,7 +745,12 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
       read_operands(I1{}, I3{});
       lds_wait6<6>(a[0], b[0]);
       products(I0{});
-      lds_wait6<0>(a[1], b[1]);                 // every LDS read of slab d is complete
+      // every LDS read of slab d is complete; the other operand buffer is tied as well so
+      // that the products just issued from it stay above this wait
+      asm volatile("s_waitcnt lgkmcnt(0)"
+                   : "+v"(a[1][0]), "+v"(a[1][1]), "+v"(a[1][2]), "+v"(a[1][3]), "+v"(b[1][0]),
+                     "+v"(b[1][1]), "+v"(a[0][0]), "+v"(a[0][1]), "+v"(a[0][2]), "+v"(a[0][3]),
+                     "+v"(b[0][0]), "+v"(b[0][1])::"memory");
       if (d + 1 < total) {
         // slab d+1 has landed (this wave's part: only the deep stream's slab d+2 is younger) ...
         if (d + 2 < total) {
