@@ -117,6 +117,41 @@ int copris_decode_attn(const void* q, const void* k_cache, const void* v_cache,
                        int64_t num_pages, float scale, int dtype, void* stream);
 
 /* ------------------------------------------------------------------------
+ * Re-prefill attention of resumed partial trajectories.
+ *
+ * Section 4, "Prioritized Resumption": the buffered partial trajectories are continued
+ * in the next rollout stage, under new weights, so their context has to be run through
+ * the model again (Section 5.3 names this re-prefilling as a cost of high concurrency).
+ * This is the attention of that pass and the refill of the KV pages: causal softmax
+ * attention over a packed batch of variable-length sequences,
+ *
+ *   out[j, h, :] = softmax_{u <= t}( scale * q[j, h, :] . k[s+u, h / g, :] ) . v[s+u, h / g, :]
+ *
+ * for token t of sequence b (s = cu_seqlens[b], j = s + t, g = Hq / Hkv), and
+ *
+ *   k_cache[block_table[b, t / P], kvh, t % P, :] = k[j, kvh, :]      (v_cache alike)
+ *
+ * after which copris_decode_attn can continue the sequence with ctx_len = its length.
+ * Cache slots that no token maps to are not written.
+ *
+ *   q    [T, Hq, D]  dtype        k, v [T, Hkv, D] dtype (packed, token-major)
+ *   cu_seqlens  [B+1] int32, cu[0] = 0, cu[B] = T
+ *   block_table [B, max_pages] int32, entries >= ceil(len_b / P) ignored
+ *   k_cache, v_cache [num_pages, Hkv, P, D] dtype, written
+ *   out  [T, Hq, D]  dtype        lse [T, Hq] fp32 or NULL
+ *   max_seqlen  an upper bound of the sequence lengths (sizes the launch)
+ *
+ * No workspace.  Compiled for dtype = COPRIS_BF16, D = 128, page_size = 16 and
+ * Hq / Hkv in {1, 2, 4, 6, 7, 8}; anything else returns COPRIS_EUNSUPPORTED.
+ * ------------------------------------------------------------------------ */
+int copris_prefill_attn(const void* q, const void* k, const void* v,
+                        const int32_t* cu_seqlens, const int32_t* block_table,
+                        void* k_cache, void* v_cache, void* out, float* lse,
+                        int B, int64_t T, int Hq, int Hkv, int D, int page_size,
+                        int max_pages, int64_t num_pages, int max_seqlen,
+                        float scale, int dtype, void* stream);
+
+/* ------------------------------------------------------------------------
  * LM head fused with log-softmax, Gumbel-max sampling and log-prob gather.
  *
  * Table 4 fixes the rollout sampler (temperature 1.0, top-p 1.0, top-k -1): one

@@ -30,6 +30,8 @@ SIGNATURES = {
     "copris_set_launch_hook": (None, [c_void_p, c_void_p]),
     "copris_decode_attn_workspace_bytes": (c_size_t, [c_int] * 6),
     "copris_decode_attn": (c_int, [c_void_p] * 8 + [c_size_t] + [c_int] * 6 + [c_int64, c_float, c_int, c_void_p]),
+    "copris_prefill_attn": (c_int, [c_void_p] * 9 + [c_int, c_int64] + [c_int] * 5 + [c_int64, c_int, c_float,
+                                                                                     c_int, c_void_p]),
     "copris_lmhead_logprob_workspace_bytes": (c_size_t, [c_int] * 3),
     "copris_lmhead_logprob": (c_int, [c_void_p] * 4 + [c_uint64, c_float] + [c_void_p] * 4
                               + [c_size_t] + [c_int] * 4 + [c_void_p]),
@@ -187,3 +189,17 @@ def lmhead_token_logprob(hidden, weight, tokens, logprob, lse, workspace, *, tem
         _ptr(workspace), workspace.numel() * workspace.element_size(), M, H, V, int(dtype),
         _stream(stream))
     _check(code, "copris_lmhead_token_logprob")
+
+
+def prefill_attn(q, k, v, cu_seqlens, block_table, k_cache, v_cache, out, lse, *, max_seqlen: int,
+                 scale: float, dtype: int, stream=None) -> None:
+    """copris_prefill_attn on device tensors (shapes as in include/copris.h)."""
+    T, Hq, D = q.shape
+    Hkv = k.shape[1]
+    num_pages, _, page_size, _ = k_cache.shape
+    B = cu_seqlens.numel() - 1
+    code = load_library().copris_prefill_attn(
+        _ptr(q), _ptr(k), _ptr(v), _ptr(cu_seqlens), _ptr(block_table), _ptr(k_cache), _ptr(v_cache),
+        _ptr(out), _ptr(lse), B, T, Hq, Hkv, D, page_size, block_table.shape[1], num_pages,
+        int(max_seqlen), float(scale), int(dtype), _stream(stream))
+    _check(code, "copris_prefill_attn")

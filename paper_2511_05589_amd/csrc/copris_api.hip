@@ -96,6 +96,31 @@ int copris_decode_attn(const void* q, const void* k_cache, const void* v_cache,
                              static_cast<hipStream_t>(stream));
 }
 
+int copris_prefill_attn(const void* q, const void* k, const void* v, const int32_t* cu_seqlens,
+                        const int32_t* block_table, void* k_cache, void* v_cache, void* out,
+                        float* lse, int B, int64_t T, int Hq, int Hkv, int D, int page_size,
+                        int max_pages, int64_t num_pages, int max_seqlen, float scale, int dtype,
+                        void* stream) {
+  if (B < 0 || T < 0 || T >= (1ll << 31)) return COPRIS_EINVAL;
+  if (B == 0 || T == 0) return (B == 0 && T != 0) ? COPRIS_EINVAL : COPRIS_OK;
+  if (!q || !k || !v || !cu_seqlens || !block_table || !k_cache || !v_cache || !out)
+    return COPRIS_EINVAL;
+  if (Hq <= 0 || Hkv <= 0 || D <= 0 || page_size <= 0 || max_pages <= 0 || num_pages <= 0 ||
+      Hq % Hkv != 0 || Hkv > 65535 || B > 65535)
+    return COPRIS_EINVAL;
+  if (max_seqlen <= 0 || static_cast<int64_t>(max_seqlen) > static_cast<int64_t>(max_pages) * page_size)
+    return COPRIS_EINVAL;
+  if (!(scale > 0.0f) || !(scale < INFINITY)) return COPRIS_EINVAL;
+  if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(k_cache) || !aligned16(v_cache) ||
+      !aligned16(out) || (lse && !aligned16(lse)))
+    return COPRIS_EINVAL;
+  if (!copris::prefill_attn_supported(Hq, Hkv, D, page_size, dtype)) return COPRIS_EUNSUPPORTED;
+  (void)hipGetLastError();
+  return copris::launch_prefill_attn(q, k, v, cu_seqlens, block_table, k_cache, v_cache, out, lse, B,
+                                     Hq, Hkv, max_pages, max_seqlen, scale,
+                                     static_cast<hipStream_t>(stream));
+}
+
 size_t copris_lmhead_logprob_workspace_bytes(int C, int H, int V) {
   if (C <= 0 || H <= 0 || V <= 0) return 0;
   return copris::lm_workspace_layout(C, H, V).total;

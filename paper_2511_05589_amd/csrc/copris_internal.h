@@ -43,6 +43,13 @@ int launch_decode_attn(const void* q, const void* k_cache, const void* v_cache,
                        void* workspace, int C, int Hq, int Hkv, int D, int page_size,
                        int max_pages, float scale, int dtype, hipStream_t stream);
 
+// ---- re-prefill attention ----------------------------------------------------
+bool prefill_attn_supported(int Hq, int Hkv, int D, int page_size, int dtype);
+int launch_prefill_attn(const void* q, const void* k, const void* v, const int32_t* cu_seqlens,
+                        const int32_t* block_table, void* k_cache, void* v_cache, void* out,
+                        float* lse, int B, int Hq, int Hkv, int max_pages, int max_seqlen,
+                        float scale, hipStream_t stream);
+
 // ---- LM head ----------------------------------------------------------------
 struct LmWorkspace {
   size_t part;      // LmPartial[C * n_tiles]

@@ -1,0 +1,263 @@
+// Re-prefill of resumed partial trajectories: causal attention over packed
+// variable-length sequences, filling the sequences' KV pages on the way
+// (Section 4, "Prioritized Resumption": buffered partial trajectories are continued in the
+// next rollout stage; Section 5.3 names their re-prefilling as a cost of high concurrency).
+//
+// bf16, head_dim 128, page 16.  One workgroup owns (sequence, kv head, tile of 32 query
+// tokens); wave h of it owns query head kvh*g + h for those 32 tokens, as two blocks of 16
+// queries.  The workgroup walks the sequence's K/V in 16-token steps up to the tile's own
+// tokens; a step's K and V rows (2 x 4 KB) are fetched once by all waves together,
+// register-staged one step ahead, parked in a double-buffered LDS tile and read by every
+// wave in operand layout.  The products are those of the decode kernel with the 16 queries
+// of a block in place of the 16-padded head group:
+//     S^T[token][query] = K[token][:] . Q[query][:]           4 x mfma 16x16x32
+//     O^T[d][query]    += V^T[d][token] . P^T[token][query]   8 x mfma 16x16x16
+// so the K and V operands are read from LDS once per step and used for both query blocks,
+// and max / sum / rescale of a query live in the lane that owns it.  Only the one or two
+// steps on the diagonal need the causal mask.  The workgroup that owns a tile also writes
+// that tile's K/V rows to the sequence's pages (each row is written by exactly one
+// workgroup).  Tiles are taken from the end of the sequences first (the long ones).
+#include <type_traits>
+
+#include "copris_device.h"
+#include "copris_internal.h"
+
+namespace copris {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+
+namespace {
+
+constexpr int kD = 128;
+constexpr int kP = 16;
+constexpr int kTileQ = 32;                        // query tokens per workgroup
+constexpr int kStepGranules = kP * kD * 2 / 16;   // 256 16-byte granules of K (and of V) per step
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+  uint32_t r;
+  asm("v_cvt_pk_bf16_f32 %0, %1, %2" : "=v"(r) : "v"(lo), "v"(hi));
+  return r;
+}
+
+// LDS position (in 16-byte granules) of granule c of token row `row` (conflict-free for the
+// row-wise writes and for both operand read patterns).
+__device__ __forceinline__ int swz_k(int row, int c) { return row * 16 + (c ^ (row & 15)); }
+__device__ __forceinline__ int swz_v(int row, int c) { return row * 16 + (c ^ ((row & 7) << 1)); }
+
+template <int G>
+__global__ __launch_bounds__(64 * G) void prefill_attn_kernel(
+    const uint16_t* __restrict__ q, const u32x4* __restrict__ k, const u32x4* __restrict__ v,
+    const int32_t* __restrict__ cu_seqlens, const int32_t* __restrict__ block_table,
+    u32x4* __restrict__ k_cache, u32x4* __restrict__ v_cache, uint16_t* __restrict__ out,
+    float* __restrict__ lse, int Hq, int Hkv, int max_pages, float scale_log2e) {
+  constexpr int kThreads = 64 * G;
+  constexpr int kStage = (2 * kStepGranules + kThreads - 1) / kThreads;   // granules a thread moves per step
+  __shared__ u32x4 lds_k[2][kStepGranules];
+  __shared__ u32x4 lds_v[2][kStepGranules];
+
+  const int b = blockIdx.z, kvh = blockIdx.y;
+  const int s0 = cu_seqlens[b];
+  const int len = cu_seqlens[b + 1] - s0;
+  const int n_tiles = (len + kTileQ - 1) / kTileQ;
+  if (static_cast<int>(blockIdx.x) >= n_tiles) return;
+  const int tile = n_tiles - 1 - blockIdx.x;        // late (long) tiles first
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int n = lane & 15;        // N index of both products: the query within a block
+  const int bq = lane >> 4;       // k-group of the MFMA operand layouts
+  const int head = kvh * G + wave;
+  const int q0 = tile * kTileQ;                      // first query token of the tile
+  const int last_step = min(2 * tile + 1, (len - 1) / kP);
+  const int32_t* bt = block_table + static_cast<size_t>(b) * max_pages;
+
+  // Q^T operands: lane (n, bq) holds Q[query n of block nb][32*kk + 8*bq .. +8]; queries past
+  // the end of the sequence are zero
+  bf16x8 qf[2][4];
+#pragma unroll
+  for (int nb = 0; nb < 2; ++nb) {
+    const int tq = q0 + 16 * nb + n;
+    const u32x4* qrow =
+        reinterpret_cast<const u32x4*>(q + (static_cast<size_t>(s0 + tq) * Hq + head) * kD);
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) {
+      u32x4 x = {0u, 0u, 0u, 0u};
+      if (tq < len) x = qrow[kk * 4 + bq];
+      qf[nb][kk] = __builtin_bit_cast(bf16x8, x);
+    }
+  }
+
+  // ---- cooperative, register-staged fetch of one step (16 tokens of K and of V) ----
+  // granule i of a step: i < 256 is K, else V; token (i & 255) >> 4, column granule i & 15.
+  // Rows past the end of the sequence re-read its last row (they are masked below).
+  u32x4 stage[kStage];
+  auto fetch = [&](int step) __attribute__((always_inline)) {
+#pragma unroll
+    for (int j = 0; j < kStage; ++j) {
+      const int i = tid + j * kThreads;
+      if (kStage * kThreads == 2 * kStepGranules || i < 2 * kStepGranules) {
+        const int tok = min(step * kP + ((i & 255) >> 4), len - 1);
+        const size_t g = (static_cast<size_t>(s0 + tok) * Hkv + kvh) * (kD * 2 / 16) + (i & 15);
+        stage[j] = (i < kStepGranules) ? k[g] : v[g];
+      }
+    }
+  };
+  // park the staged step in LDS buffer `buf`; a step of the tile's own tokens also goes to
+  // the sequence's page (slots past the end of the sequence are left alone)
+  auto park = [&](int step, int buf) __attribute__((always_inline)) {
+    const bool own = step >= 2 * tile;
+    const size_t page = own ? (static_cast<size_t>(bt[step]) * Hkv + kvh) * kStepGranules : 0;
+#pragma unroll
+    for (int j = 0; j < kStage; ++j) {
+      const int i = tid + j * kThreads;
+      if (kStage * kThreads == 2 * kStepGranules || i < 2 * kStepGranules) {
+        const int gi = i & 255, tok = gi >> 4, c = gi & 15;
+        if (i < kStepGranules) {
+          lds_k[buf][swz_k(tok, c)] = stage[j];
+          if (own && step * kP + tok < len) k_cache[page + gi] = stage[j];
+        } else {
+          lds_v[buf][swz_v(tok, c)] = stage[j];
+          if (own && step * kP + tok < len) v_cache[page + gi] = stage[j];
+        }
+      }
+    }
+  };
+
+  float m_run[2] = {-INFINITY, -INFINITY}, l_run[2] = {0.0f, 0.0f};
+  f32x4 o[2][8];
+#pragma unroll
+  for (int i = 0; i < 16; ++i) o[i >> 3][i & 7] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+
+  fetch(0);
+  park(0, 0);
+  __syncthreads();
+
+  for (int step = 0; step <= last_step; ++step) {
+    const int buf = step & 1;
+    if (step < last_step) fetch(step + 1);
+
+    // K rows as the A operand of the score product (token = lane & 15), read once for both
+    // query blocks
+    bf16x8 kf[4];
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk)
+      kf[kk] = __builtin_bit_cast(bf16x8, lds_k[buf][swz_k(n, 4 * kk + bq)]);
+    // V^T as the A operand of the value product through the transposing read (lane supplies
+    // row 4*bq + n/4, columns 16*dt + 4*(n%4) .. +3)
+    s16x4 vf[8];
+    {
+      const int vrow = 4 * bq + (n >> 2);
+      const char* vbase = reinterpret_cast<const char*>(lds_v[buf]) + (n & 1) * 8;
+#pragma unroll
+      for (int dt = 0; dt < 8; ++dt) {
+        const char* addr = vbase + swz_v(vrow, 2 * dt + ((n & 3) >> 1)) * 16;
+        vf[dt] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(addr));
+      }
+    }
+    const bool tail = step * kP + kP > len;          // tokens past the end of the sequence
+#pragma unroll
+    for (int nb = 0; nb < 2; ++nb) {
+      if (step > 2 * tile + nb) continue;            // every token of the step is in the block's future
+      f32x4 sc = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+      for (int kk = 0; kk < 4; ++kk)
+        sc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[kk], qf[nb][kk], sc, 0, 0, 0);
+      // this lane: query n of the block, tokens 4*bq .. 4*bq+3 of the step
+      float t[4];
+#pragma unroll
+      for (int rr = 0; rr < 4; ++rr) t[rr] = sc[rr] * scale_log2e;
+      if (step == 2 * tile + nb || tail) {
+        const int tq = q0 + 16 * nb + n;
+#pragma unroll
+        for (int rr = 0; rr < 4; ++rr) {
+          const int tk = step * kP + 4 * bq + rr;
+          t[rr] = (tk <= tq && tk < len) ? t[rr] : -INFINITY;
+        }
+      }
+      float mx = fmaxf(fmaxf(t[0], t[1]), fmaxf(t[2], t[3]));
+      mx = fmaxf(mx, __shfl_xor(mx, 16, kWave));
+      mx = fmaxf(mx, __shfl_xor(mx, 32, kWave));
+      const float m_new = fmaxf(m_run[nb], mx);
+      const float alpha = __builtin_amdgcn_exp2f(m_run[nb] - m_new);
+      m_run[nb] = m_new;
+      float p[4];
+#pragma unroll
+      for (int rr = 0; rr < 4; ++rr) p[rr] = __builtin_amdgcn_exp2f(t[rr] - m_new);
+      l_run[nb] = l_run[nb] * alpha + ((p[0] + p[1]) + (p[2] + p[3]));
+      const uint2 pk = make_uint2(pack_bf16x2(p[0], p[1]), pack_bf16x2(p[2], p[3]));
+      const s16x4 pf = __builtin_bit_cast(s16x4, pk);
+      if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {
+#pragma unroll
+        for (int dt = 0; dt < 8; ++dt) o[nb][dt] *= alpha;
+      }
+#pragma unroll
+      for (int dt = 0; dt < 8; ++dt)
+        o[nb][dt] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(vf[dt], pf, o[nb][dt], 0, 0, 0);
+    }
+
+    if (step < last_step) park(step + 1, buf ^ 1);   // that buffer was last read one step ago
+    __syncthreads();
+  }
+
+  // normalise and store: lane (n, bq) owns d = 16*dt + 4*bq + r of query n
+#pragma unroll
+  for (int nb = 0; nb < 2; ++nb) {
+    const int tq = q0 + 16 * nb + n;
+    float l_all = l_run[nb];
+    l_all += __shfl_xor(l_all, 16, kWave);
+    l_all += __shfl_xor(l_all, 32, kWave);
+    if (tq < len) {
+      const float inv = 1.0f / l_all;
+      uint16_t* dst = out + (static_cast<size_t>(s0 + tq) * Hq + head) * kD + 4 * bq;
+#pragma unroll
+      for (int dt = 0; dt < 8; ++dt) {
+        const uint2 w = make_uint2(pack_bf16x2(o[nb][dt][0] * inv, o[nb][dt][1] * inv),
+                                   pack_bf16x2(o[nb][dt][2] * inv, o[nb][dt][3] * inv));
+        *reinterpret_cast<uint2*>(dst + 16 * dt) = w;
+      }
+      if (lse != nullptr && bq == 0)
+        lse[static_cast<size_t>(s0 + tq) * Hq + head] = (m_run[nb] + __builtin_amdgcn_logf(l_all)) * kLn2;
+    }
+  }
+}
+
+}  // namespace
+
+bool prefill_attn_supported(int Hq, int Hkv, int D, int page_size, int dtype) {
+  if (dtype != 1 || D != kD || page_size != kP || Hq % Hkv != 0) return false;
+  const int g = Hq / Hkv;
+  return g == 1 || g == 2 || g == 4 || g == 6 || g == 7 || g == 8;
+}
+
+int launch_prefill_attn(const void* q, const void* k, const void* v, const int32_t* cu_seqlens,
+                        const int32_t* block_table, void* k_cache, void* v_cache, void* out,
+                        float* lse, int B, int Hq, int Hkv, int max_pages, int max_seqlen,
+                        float scale, hipStream_t stream) {
+  const int g = Hq / Hkv;
+  const dim3 grid((max_seqlen + kTileQ - 1) / kTileQ, Hkv, B);
+  const float scale_log2e = scale * kLog2e;
+#define COPRIS_PREFILL(G)                                                                        \
+  hipLaunchKernelGGL(prefill_attn_kernel<G>, grid, dim3(64 * G), 0, stream,                      \
+                     static_cast<const uint16_t*>(q), static_cast<const u32x4*>(k),              \
+                     static_cast<const u32x4*>(v), cu_seqlens, block_table,                      \
+                     static_cast<u32x4*>(k_cache), static_cast<u32x4*>(v_cache),                 \
+                     static_cast<uint16_t*>(out), lse, Hq, Hkv, max_pages, scale_log2e)
+  COPRIS_PRE("prefill_attn_kernel");
+  switch (g) {
+    case 1: COPRIS_PREFILL(1); break;
+    case 2: COPRIS_PREFILL(2); break;
+    case 4: COPRIS_PREFILL(4); break;
+    case 6: COPRIS_PREFILL(6); break;
+    case 7: COPRIS_PREFILL(7); break;
+    default: COPRIS_PREFILL(8); break;
+  }
+#undef COPRIS_PREFILL
+  COPRIS_POST("prefill_attn_kernel");
+  return 0;
+}
+
+}  // namespace copris

@@ -265,3 +265,50 @@ def run_token_logprob(hidden, weight, tokens, temperature: float, dtype: str):
     d.run()
     torch.cuda.synchronize()
     return d.logprob.cpu().numpy(), d.lse.cpu().numpy()
+
+
+@dataclass
+class PrefillDevice:
+    q: torch.Tensor
+    k: torch.Tensor
+    v: torch.Tensor
+    cu_seqlens: torch.Tensor
+    block_table: torch.Tensor
+    k_cache: torch.Tensor
+    v_cache: torch.Tensor
+    out: torch.Tensor
+    lse: torch.Tensor
+    max_seqlen: int
+    scale: float
+    dtype: int
+
+    def run(self, stream=None):
+        binding.prefill_attn(self.q, self.k, self.v, self.cu_seqlens, self.block_table, self.k_cache,
+                             self.v_cache, self.out, self.lse, max_seqlen=self.max_seqlen,
+                             scale=self.scale, dtype=self.dtype, stream=stream)
+
+
+def stage_prefill_attn(b: dict, dtype: str, device=None) -> PrefillDevice:
+    """b: q [T,Hq,D], k, v [T,Hkv,D] (storage arrays), cu_seqlens, block_table, num_pages,
+    page_size, scale.  The caches start as NaN so that untouched slots stay recognisable."""
+    device = device or require_gpu()
+    q, k, v = (to_device(b[x], device=device) for x in ("q", "k", "v"))
+    T, Hq, D = q.shape
+    Hkv = k.shape[1]
+    shape = (int(b["num_pages"]), Hkv, int(b["page_size"]), D)
+    kc = torch.full(shape, float("nan"), dtype=q.dtype, device=device)
+    vc = torch.full(shape, float("nan"), dtype=q.dtype, device=device)
+    out = torch.full_like(q, float("nan"))
+    lse = torch.full((max(T, 1), Hq), float("nan"), dtype=torch.float32, device=device)
+    lens = np.diff(np.asarray(b["cu_seqlens"], dtype=np.int64))
+    return PrefillDevice(q, k, v, to_device(np.asarray(b["cu_seqlens"], dtype=np.int32), device=device),
+                         to_device(np.asarray(b["block_table"], dtype=np.int32), device=device), kc, vc,
+                         out, lse, int(max(lens.max(initial=1), 1)), float(b["scale"]), dtype_code(dtype))
+
+
+def run_prefill_attn(b: dict, dtype: str):
+    """Returns (out fp32 [T,Hq,D], lse [T,Hq], k_cache, v_cache as float32 arrays)."""
+    d = stage_prefill_attn(b, dtype)
+    d.run()
+    torch.cuda.synchronize()
+    return (out_to_f32(d.out), d.lse.cpu().numpy(), out_to_f32(d.k_cache), out_to_f32(d.v_cache))

@@ -310,6 +310,22 @@ def make_token_logprob_inputs(cfg: DecodeConfig, M: int) -> dict:
             "temperature": float(cfg.temperature)}
 
 
+def make_prefill_case(seed: int, lens, Hq: int, Hkv: int, D: int, dtype: str, page_size: int = 16,
+                      spare_frac: float = 0.25) -> dict:
+    """Resumed partial trajectories to re-prefill: packed q / k / v ~ N(0,1) for sequences of
+    the given lengths, and a block table over seeded, randomly interleaved physical pages."""
+    rng_perm, rng_q, rng_k, rng_v = np.random.default_rng(seed).spawn(4)
+    lens = np.asarray(lens, dtype=np.int32)
+    T = int(lens.sum())
+    cu = np.zeros(lens.size + 1, dtype=np.int32)
+    np.cumsum(lens, out=cu[1:])
+    bt, num_pages = make_block_table(lens, page_size, spare_frac, rng_perm)
+    return {"q": _normal_storage(rng_q, (T, Hq, D), dtype), "k": _normal_storage(rng_k, (T, Hkv, D), dtype),
+            "v": _normal_storage(rng_v, (T, Hkv, D), dtype), "cu_seqlens": cu, "lens": lens,
+            "block_table": bt, "num_pages": num_pages, "page_size": page_size,
+            "scale": float(1.0 / np.sqrt(D)), "Hq": Hq, "Hkv": Hkv, "D": D, "dtype": dtype}
+
+
 def make_small_decode_case(seed: int, C: int, Hq: int, Hkv: int, D: int, dtype: str,
                            page_size: int, ctx_len, *, spare_frac: float = 0.25,
                            max_pages: Optional[int] = None, poison: bool = True) -> dict:

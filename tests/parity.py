@@ -172,3 +172,34 @@ def check_token_logprob(logprob, lse, ref, what=""):
     lerr = np.abs(lse.astype(np.float64) - ref["lse"]).max()
     assert lerr <= LOGPROB_TOL, f"{what}: lse error {lerr:.3e}"
     return err
+
+
+# ---- re-prefill attention ------------------------------------------------------
+def oracle_prefill(b, dtype):
+    """Oracle outputs for every token, plus the oracle-filled caches (fp32 views of the
+    storage values, NaN where no token maps)."""
+    q, k, v = (W.to_f32(b[x], dtype) for x in ("q", "k", "v"))
+    out, lse = O.prefill_attn(q, k, v, b["cu_seqlens"], b["scale"])
+    kc, vc = oracle_page_fill(b, dtype)
+    return out, lse, kc, vc
+
+
+def oracle_page_fill(b, dtype):
+    k, v = W.to_f32(b["k"], dtype), W.to_f32(b["v"], dtype)
+    shape = (int(b["num_pages"]), k.shape[1], int(b["page_size"]), k.shape[2])
+    kc = np.full(shape, np.nan, dtype=np.float32)
+    vc = np.full(shape, np.nan, dtype=np.float32)
+    O.kv_page_fill(k, v, b["cu_seqlens"], b["block_table"], kc, vc)
+    return kc, vc
+
+
+def oracle_prefill_rows(b, dtype, seq_tok, kc, vc):
+    """Oracle rows for sampled (sequence, token) pairs through the decode oracle over the
+    oracle-filled pages (the two oracles are pinned to each other on the CPU)."""
+    q = W.to_f32(b["q"], dtype)
+    cu = np.asarray(b["cu_seqlens"], dtype=np.int64)
+    seqs = np.array([s for s, _ in seq_tok])
+    toks = np.array([t for _, t in seq_tok])
+    rows = cu[seqs] + toks
+    out, lse = O.decode_attn(q[rows], kc, vc, np.asarray(b["block_table"])[seqs], toks + 1, b["scale"])
+    return rows, out, lse
