@@ -42,6 +42,8 @@ def parse_args():
                          "FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run)")
     ap.add_argument("--token-logprob-m", type=int, default=8192,
                     help="positions in the micro-batch of the given-token log-prob measurement")
+    ap.add_argument("--prefill-seqs", type=int, default=16,
+                    help="resumed trajectories in the re-prefill attention measurement")
     return ap.parse_args()
 
 
@@ -261,6 +263,33 @@ def main():
             "TFLOPs": round(flops / (tl_ms * 1e-3) / 1e12, 1),
             "mfma_frac": round(flops / (tl_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
             "workload": f"{M} positions x LM head {cfg.H}x{cfg.V} bf16, given tokens"}
+    # ---- outside the step: re-prefill attention of resumed partial trajectories (one
+    # layer): a handful of buffered trajectories with the config's length recipe ----
+    if args.config == 2:
+        plens = W.make_ctx_len(cfg, np.random.default_rng(cfg.seed + 5))[:args.prefill_seqs]
+        pb = W.make_prefill_case(cfg.seed + 6, plens, cfg.Hq, cfg.Hkv, cfg.D, cfg.dtype)
+        pd = runner.stage_prefill_attn(pb, cfg.dtype, dev)
+        for _ in range(2):
+            pd.run(stream)
+        torch.cuda.synchronize()
+        reps = max(3, args.steps // 5)
+        p0e, p1e = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        p0e.record(stream)
+        for _ in range(reps):
+            pd.run(stream)
+        p1e.record(stream)
+        torch.cuda.synchronize()
+        pf_ms = p0e.elapsed_time(p1e) / reps
+        L = plens.astype(np.float64)
+        pflops = float((4.0 * cfg.Hq * cfg.D * L * (L + 1) / 2).sum())
+        result["extras"]["prefill_attn"] = {
+            "call_ms": round(pf_ms, 3), "tokens": int(plens.sum()),
+            "tokens_per_s": round(float(plens.sum()) / (pf_ms * 1e-3), 1),
+            "TFLOPs": round(pflops / (pf_ms * 1e-3) / 1e12, 1),
+            "mfma_frac": round(pflops / (pf_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
+            "workload": f"{len(plens)} resumed trajectories, lengths {int(plens.min())}..{int(plens.max())}, "
+                        f"{cfg.Hq}q/{cfg.Hkv}kv heads, causal, one layer"}
+        del pd, pb
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(cfg, inp, args.cpu_sample)
     print(json.dumps(result))
