@@ -142,7 +142,7 @@ int copris_decode_attn(const void* q, const void* k_cache, const void* v_cache,
  *   max_seqlen  an upper bound of the sequence lengths (sizes the launch)
  *
  * No workspace.  Compiled for dtype = COPRIS_BF16, D = 128, page_size = 16 and
- * Hq / Hkv in {1, 2, 4, 6, 7, 8}; anything else returns COPRIS_EUNSUPPORTED.
+ * Hq / Hkv <= 8; anything else returns COPRIS_EUNSUPPORTED.
  * ------------------------------------------------------------------------ */
 int copris_prefill_attn(const void* q, const void* k, const void* v,
                         const int32_t* cu_seqlens, const int32_t* block_table,

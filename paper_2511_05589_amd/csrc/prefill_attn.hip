@@ -49,14 +49,21 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
 __device__ __forceinline__ int swz_k(int row, int c) { return row * 16 + (c ^ (row & 15)); }
 __device__ __forceinline__ int swz_v(int row, int c) { return row * 16 + (c ^ ((row & 7) << 1)); }
 
+// Threads of a workgroup: G waves where that divides the 512 granules of a step evenly,
+// else eight waves of which the first G compute and all fetch.
+template <int G> struct PrefillThreads {
+  static constexpr int value = (8 % G == 0) ? 64 * G : 512;
+};
+
 template <int G>
-__global__ __launch_bounds__(64 * G) void prefill_attn_kernel(
+__global__ __launch_bounds__(PrefillThreads<G>::value) void prefill_attn_kernel(
     const uint16_t* __restrict__ q, const u32x4* __restrict__ k, const u32x4* __restrict__ v,
     const int32_t* __restrict__ cu_seqlens, const int32_t* __restrict__ block_table,
     u32x4* __restrict__ k_cache, u32x4* __restrict__ v_cache, uint16_t* __restrict__ out,
     float* __restrict__ lse, int Hq, int Hkv, int max_pages, float scale_log2e) {
-  constexpr int kThreads = 64 * G;
-  constexpr int kStage = (2 * kStepGranules + kThreads - 1) / kThreads;   // granules a thread moves per step
+  constexpr int kThreads = PrefillThreads<G>::value;
+  constexpr int kStage = 2 * kStepGranules / kThreads;   // granules a thread moves per step
+  static_assert(kStage * kThreads == 2 * kStepGranules, "a step's granules divide evenly over the threads");
   __shared__ u32x4 lds_k[2][kStepGranules];
   __shared__ u32x4 lds_v[2][kStepGranules];
 
@@ -70,7 +77,8 @@ __global__ __launch_bounds__(64 * G) void prefill_attn_kernel(
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int n = lane & 15;        // N index of both products: the query within a block
   const int bq = lane >> 4;       // k-group of the MFMA operand layouts
-  const int head = kvh * G + wave;
+  const bool computes = wave < G;                 // (the other waves only move data)
+  const int head = kvh * G + min(wave, G - 1);
   const int q0 = tile * kTileQ;                      // first query token of the tile
   const int last_step = min(2 * tile + 1, (len - 1) / kP);
   const int32_t* bt = block_table + static_cast<size_t>(b) * max_pages;
@@ -86,7 +94,7 @@ __global__ __launch_bounds__(64 * G) void prefill_attn_kernel(
 #pragma unroll
     for (int kk = 0; kk < 4; ++kk) {
       u32x4 x = {0u, 0u, 0u, 0u};
-      if (tq < len) x = qrow[kk * 4 + bq];
+      if (computes && tq < len) x = qrow[kk * 4 + bq];
       qf[nb][kk] = __builtin_bit_cast(bf16x8, x);
     }
   }
@@ -94,35 +102,34 @@ __global__ __launch_bounds__(64 * G) void prefill_attn_kernel(
   // ---- cooperative, register-staged fetch of one step (16 tokens of K and of V) ----
   // granule i of a step: i < 256 is K, else V; token (i & 255) >> 4, column granule i & 15.
   // Rows past the end of the sequence re-read its last row (they are masked below).
-  u32x4 stage[kStage];
-  auto fetch = [&](int step) __attribute__((always_inline)) {
+  // two register stages: the fetch of step s+2 is in flight while step s+1 is parked
+  u32x4 stage_a[kStage], stage_b[kStage];
+  auto fetch = [&](u32x4 (&stage)[kStage], int step) __attribute__((always_inline)) {
+    // steps past the last one re-read the last token's rows (never parked)
 #pragma unroll
     for (int j = 0; j < kStage; ++j) {
       const int i = tid + j * kThreads;
-      if (kStage * kThreads == 2 * kStepGranules || i < 2 * kStepGranules) {
-        const int tok = min(step * kP + ((i & 255) >> 4), len - 1);
-        const size_t g = (static_cast<size_t>(s0 + tok) * Hkv + kvh) * (kD * 2 / 16) + (i & 15);
-        stage[j] = (i < kStepGranules) ? k[g] : v[g];
-      }
+      const int tok = min(step * kP + ((i & 255) >> 4), len - 1);
+      const size_t g = (static_cast<size_t>(s0 + tok) * Hkv + kvh) * (kD * 2 / 16) + (i & 15);
+      const u32x4* src = (i < kStepGranules) ? k : v;
+      stage[j] = src[g];
     }
   };
   // park the staged step in LDS buffer `buf`; a step of the tile's own tokens also goes to
   // the sequence's page (slots past the end of the sequence are left alone)
-  auto park = [&](int step, int buf) __attribute__((always_inline)) {
-    const bool own = step >= 2 * tile;
+  auto park = [&](u32x4 (&stage)[kStage], int step, int buf, auto may_own) __attribute__((always_inline)) {
+    const bool own = decltype(may_own)::value && step >= 2 * tile;
     const size_t page = own ? (static_cast<size_t>(bt[step]) * Hkv + kvh) * kStepGranules : 0;
 #pragma unroll
     for (int j = 0; j < kStage; ++j) {
       const int i = tid + j * kThreads;
-      if (kStage * kThreads == 2 * kStepGranules || i < 2 * kStepGranules) {
-        const int gi = i & 255, tok = gi >> 4, c = gi & 15;
-        if (i < kStepGranules) {
-          lds_k[buf][swz_k(tok, c)] = stage[j];
-          if (own && step * kP + tok < len) k_cache[page + gi] = stage[j];
-        } else {
-          lds_v[buf][swz_v(tok, c)] = stage[j];
-          if (own && step * kP + tok < len) v_cache[page + gi] = stage[j];
-        }
+      const int gi = i & 255, tok = gi >> 4, c = gi & 15;
+      if (i < kStepGranules) {
+        lds_k[buf][swz_k(tok, c)] = stage[j];
+        if (own && step * kP + tok < len) k_cache[page + gi] = stage[j];
+      } else {
+        lds_v[buf][swz_v(tok, c)] = stage[j];
+        if (own && step * kP + tok < len) v_cache[page + gi] = stage[j];
       }
     }
   };
@@ -132,75 +139,112 @@ __global__ __launch_bounds__(64 * G) void prefill_attn_kernel(
 #pragma unroll
   for (int i = 0; i < 16; ++i) o[i >> 3][i & 7] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
 
-  fetch(0);
-  park(0, 0);
+  fetch(stage_a, 0);
+  fetch(stage_b, 1);
+  park(stage_a, 0, 0, std::true_type{});
   __syncthreads();
 
-  for (int step = 0; step <= last_step; ++step) {
+  // one step; `cur` holds the rows of step+1 (fetched a step ago), `nxt` is free and takes
+  // the fetch of step+2 (unconditional: a fetch past the end stays in bounds and is dropped)
+  // diag = false: a step strictly before the tile's own tokens (no mask, no page write, and
+  // the step after it exists)
+  auto do_step = [&](u32x4 (&cur)[kStage], u32x4 (&nxt)[kStage], const int step, auto diag) __attribute__((always_inline)) {
+    constexpr bool kDiag = decltype(diag)::value;
     const int buf = step & 1;
-    if (step < last_step) fetch(step + 1);
+    fetch(nxt, step + 2);
 
-    // K rows as the A operand of the score product (token = lane & 15), read once for both
-    // query blocks
-    bf16x8 kf[4];
-#pragma unroll
-    for (int kk = 0; kk < 4; ++kk)
-      kf[kk] = __builtin_bit_cast(bf16x8, lds_k[buf][swz_k(n, 4 * kk + bq)]);
-    // V^T as the A operand of the value product through the transposing read (lane supplies
-    // row 4*bq + n/4, columns 16*dt + 4*(n%4) .. +3)
-    s16x4 vf[8];
-    {
-      const int vrow = 4 * bq + (n >> 2);
-      const char* vbase = reinterpret_cast<const char*>(lds_v[buf]) + (n & 1) * 8;
-#pragma unroll
-      for (int dt = 0; dt < 8; ++dt) {
-        const char* addr = vbase + swz_v(vrow, 2 * dt + ((n & 3) >> 1)) * 16;
-        vf[dt] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(addr));
-      }
-    }
-    const bool tail = step * kP + kP > len;          // tokens past the end of the sequence
-#pragma unroll
-    for (int nb = 0; nb < 2; ++nb) {
-      if (step > 2 * tile + nb) continue;            // every token of the step is in the block's future
-      f32x4 sc = {0.0f, 0.0f, 0.0f, 0.0f};
-#pragma unroll
+    if (computes) {
+      // K rows as the A operand of the score product (token = lane & 15), read once for both
+      // query blocks
+      bf16x8 kf[4];
+  #pragma unroll
       for (int kk = 0; kk < 4; ++kk)
-        sc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[kk], qf[nb][kk], sc, 0, 0, 0);
-      // this lane: query n of the block, tokens 4*bq .. 4*bq+3 of the step
-      float t[4];
-#pragma unroll
-      for (int rr = 0; rr < 4; ++rr) t[rr] = sc[rr] * scale_log2e;
-      if (step == 2 * tile + nb || tail) {
-        const int tq = q0 + 16 * nb + n;
-#pragma unroll
-        for (int rr = 0; rr < 4; ++rr) {
-          const int tk = step * kP + 4 * bq + rr;
-          t[rr] = (tk <= tq && tk < len) ? t[rr] : -INFINITY;
+        kf[kk] = __builtin_bit_cast(bf16x8, lds_k[buf][swz_k(n, 4 * kk + bq)]);
+      // V^T as the A operand of the value product through the transposing read (lane supplies
+      // row 4*bq + n/4, columns 16*dt + 4*(n%4) .. +3)
+      s16x4 vf[8];
+      {
+        const int vrow = 4 * bq + (n >> 2);
+        const char* vbase = reinterpret_cast<const char*>(lds_v[buf]) + (n & 1) * 8;
+  #pragma unroll
+        for (int dt = 0; dt < 8; ++dt) {
+          const char* addr = vbase + swz_v(vrow, 2 * dt + ((n & 3) >> 1)) * 16;
+          vf[dt] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(addr));
         }
       }
-      float mx = fmaxf(fmaxf(t[0], t[1]), fmaxf(t[2], t[3]));
-      mx = fmaxf(mx, __shfl_xor(mx, 16, kWave));
-      mx = fmaxf(mx, __shfl_xor(mx, 32, kWave));
-      const float m_new = fmaxf(m_run[nb], mx);
-      const float alpha = __builtin_amdgcn_exp2f(m_run[nb] - m_new);
-      m_run[nb] = m_new;
-      float p[4];
-#pragma unroll
-      for (int rr = 0; rr < 4; ++rr) p[rr] = __builtin_amdgcn_exp2f(t[rr] - m_new);
-      l_run[nb] = l_run[nb] * alpha + ((p[0] + p[1]) + (p[2] + p[3]));
-      const uint2 pk = make_uint2(pack_bf16x2(p[0], p[1]), pack_bf16x2(p[2], p[3]));
-      const s16x4 pf = __builtin_bit_cast(s16x4, pk);
-      if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {
-#pragma unroll
-        for (int dt = 0; dt < 8; ++dt) o[nb][dt] *= alpha;
+      const bool tail = kDiag && step * kP + kP > len;  // tokens past the end of the sequence
+      // Both query blocks go through every stage together (two independent dependency chains
+      // for the scheduler to interleave).  A block whose queries all lie before the step's
+      // tokens is fully masked: its weights are exp2(-inf - m) = 0 and its state is unchanged
+      // (m is finite from step 0 on: token 0 is visible to every query).
+      f32x4 sc[2];
+  #pragma unroll
+      for (int nb = 0; nb < 2; ++nb) {
+        sc[nb] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+  #pragma unroll
+        for (int kk = 0; kk < 4; ++kk)
+          sc[nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[kk], qf[nb][kk], sc[nb], 0, 0, 0);
       }
-#pragma unroll
-      for (int dt = 0; dt < 8; ++dt)
-        o[nb][dt] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(vf[dt], pf, o[nb][dt], 0, 0, 0);
+      // this lane: query n of each block, tokens 4*bq .. 4*bq+3 of the step
+      float t[2][4];
+  #pragma unroll
+      for (int nb = 0; nb < 2; ++nb)
+  #pragma unroll
+        for (int rr = 0; rr < 4; ++rr) t[nb][rr] = sc[nb][rr] * scale_log2e;
+      if (kDiag && (step >= 2 * tile || tail)) {       // a step on the diagonal or at the end
+  #pragma unroll
+        for (int nb = 0; nb < 2; ++nb) {
+          const int tq = q0 + 16 * nb + n;
+  #pragma unroll
+          for (int rr = 0; rr < 4; ++rr) {
+            const int tk = step * kP + 4 * bq + rr;
+            t[nb][rr] = (tk <= tq && tk < len) ? t[nb][rr] : -INFINITY;
+          }
+        }
+      }
+      float alpha[2];
+      s16x4 pf[2];
+  #pragma unroll
+      for (int nb = 0; nb < 2; ++nb) {
+        float mx = fmaxf(fmaxf(t[nb][0], t[nb][1]), fmaxf(t[nb][2], t[nb][3]));
+        mx = fmaxf(mx, __shfl_xor(mx, 16, kWave));
+        mx = fmaxf(mx, __shfl_xor(mx, 32, kWave));
+        const float m_new = fmaxf(m_run[nb], mx);
+        alpha[nb] = __builtin_amdgcn_exp2f(m_run[nb] - m_new);
+        m_run[nb] = m_new;
+        float p[4];
+  #pragma unroll
+        for (int rr = 0; rr < 4; ++rr) p[rr] = __builtin_amdgcn_exp2f(t[nb][rr] - m_new);
+        l_run[nb] = l_run[nb] * alpha[nb] + ((p[0] + p[1]) + (p[2] + p[3]));
+        const uint2 pk = make_uint2(pack_bf16x2(p[0], p[1]), pack_bf16x2(p[2], p[3]));
+        pf[nb] = __builtin_bit_cast(s16x4, pk);
+      }
+      if (__builtin_amdgcn_ballot_w64(alpha[0] != 1.0f || alpha[1] != 1.0f) != 0) {
+  #pragma unroll
+        for (int i = 0; i < 16; ++i) o[i >> 3][i & 7] *= alpha[i >> 3];
+      }
+  #pragma unroll
+      for (int dt = 0; dt < 8; ++dt) {
+        o[0][dt] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(vf[dt], pf[0], o[0][dt], 0, 0, 0);
+        o[1][dt] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(vf[dt], pf[1], o[1][dt], 0, 0, 0);
+      }
     }
-
-    if (step < last_step) park(step + 1, buf ^ 1);   // that buffer was last read one step ago
+    // park step+1; that LDS buffer was last read one step ago
+    if (kDiag) {
+      if (step < last_step) park(cur, step + 1, buf ^ 1, std::true_type{});
+    } else {
+      park(cur, step + 1, buf ^ 1, std::false_type{});
+    }
     __syncthreads();
+  };
+  int step = 0;
+  for (; step + 1 <= 2 * tile - 2; step += 2) {   // pairs of steps before the diagonal
+    do_step(stage_b, stage_a, step, std::false_type{});
+    do_step(stage_a, stage_b, step + 1, std::false_type{});
+  }
+  for (; step <= last_step; step += 2) {          // the last two to four steps
+    do_step(stage_b, stage_a, step, std::true_type{});
+    if (step + 1 <= last_step) do_step(stage_a, stage_b, step + 1, std::true_type{});
   }
 
   // normalise and store: lane (n, bq) owns d = 16*dt + 4*bq + r of query n
@@ -210,7 +254,7 @@ __global__ __launch_bounds__(64 * G) void prefill_attn_kernel(
     float l_all = l_run[nb];
     l_all += __shfl_xor(l_all, 16, kWave);
     l_all += __shfl_xor(l_all, 32, kWave);
-    if (tq < len) {
+    if (computes && tq < len) {
       const float inv = 1.0f / l_all;
       uint16_t* dst = out + (static_cast<size_t>(s0 + tq) * Hq + head) * kD + 4 * bq;
 #pragma unroll
@@ -230,7 +274,7 @@ __global__ __launch_bounds__(64 * G) void prefill_attn_kernel(
 bool prefill_attn_supported(int Hq, int Hkv, int D, int page_size, int dtype) {
   if (dtype != 1 || D != kD || page_size != kP || Hq % Hkv != 0) return false;
   const int g = Hq / Hkv;
-  return g == 1 || g == 2 || g == 4 || g == 6 || g == 7 || g == 8;
+  return g >= 1 && g <= 8;
 }
 
 int launch_prefill_attn(const void* q, const void* k, const void* v, const int32_t* cu_seqlens,
@@ -241,7 +285,7 @@ int launch_prefill_attn(const void* q, const void* k, const void* v, const int32
   const dim3 grid((max_seqlen + kTileQ - 1) / kTileQ, Hkv, B);
   const float scale_log2e = scale * kLog2e;
 #define COPRIS_PREFILL(G)                                                                        \
-  hipLaunchKernelGGL(prefill_attn_kernel<G>, grid, dim3(64 * G), 0, stream,                      \
+  hipLaunchKernelGGL(prefill_attn_kernel<G>, grid, dim3(PrefillThreads<G>::value), 0, stream,    \
                      static_cast<const uint16_t*>(q), static_cast<const u32x4*>(k),              \
                      static_cast<const u32x4*>(v), cu_seqlens, block_table,                      \
                      static_cast<u32x4*>(k_cache), static_cast<u32x4*>(v_cache),                 \
@@ -250,7 +294,9 @@ int launch_prefill_attn(const void* q, const void* k, const void* v, const int32
   switch (g) {
     case 1: COPRIS_PREFILL(1); break;
     case 2: COPRIS_PREFILL(2); break;
+    case 3: COPRIS_PREFILL(3); break;
     case 4: COPRIS_PREFILL(4); break;
+    case 5: COPRIS_PREFILL(5); break;
     case 6: COPRIS_PREFILL(6); break;
     case 7: COPRIS_PREFILL(7); break;
     default: COPRIS_PREFILL(8); break;

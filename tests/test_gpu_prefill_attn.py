@@ -24,7 +24,7 @@ def _check_all(R, b, what):
     np.testing.assert_array_equal(vc, ref_vc)
 
 
-@pytest.mark.parametrize("Hq,Hkv", [(28, 4), (12, 2), (4, 4), (8, 4), (16, 4), (8, 1)])
+@pytest.mark.parametrize("Hq,Hkv", [(28, 4), (12, 2), (4, 4), (8, 4), (16, 4), (8, 1), (6, 2), (5, 1)])
 def test_ragged_lengths_every_group_size(R, Hq, Hkv):
     # lengths around the page, the query-block and the tile boundaries
     lens = [1, 15, 16, 17, 31, 32, 33, 47, 48, 49, 64, 100, 257]
@@ -96,7 +96,7 @@ def test_resumed_trajectories_at_the_7b_shape_on_sampled_tokens(R):
 
 def test_unsupported_shapes_are_refused(R):
     from paper_2511_05589_amd import binding
-    b = W.make_prefill_case(14, [20], 12, 4, 128, W.BF16)       # group of 3: not compiled
+    b = W.make_prefill_case(14, [20], 18, 2, 128, W.BF16)       # group of 9: not compiled
     with pytest.raises(binding.CoprisError) as e:
         R.run_prefill_attn(b, W.BF16)
     assert e.value.code == binding.COPRIS_EUNSUPPORTED
