@@ -5,15 +5,15 @@
 // and cut into equal contiguous shares, one per persistent wavefront ("stream-K"): the
 // split is balanced to one page whatever the length distribution, a 32k-token resumed
 // trajectory is simply spread over many wavefronts, and nothing is scheduled at run time.
-//   scan kernel    ctx_len -> page prefix sums, slots per wavefront
-//   fill kernel    block table -> flat slot list (physical page, kv head, sequence,
-//                  tokens valid in the page)
-//   split kernel   one wavefront per share: walks its slots with a three-page-deep
-//                  register prefetch; whenever the (sequence, kv head) changes it writes
-//                  the online-softmax partial (running max, weight sum, weighted value
-//                  sum) of the g query heads that share the kv head
-//   merge kernel   per (sequence, query head): log-sum-exp combination of the partials
-//                  in share order, normalisation, store
+//   scan kernel    ctx_len -> page prefix sums, slots per wavefront, and each wavefront's
+//                  start cursor (sequence, kv head, page) in the slot stream
+//   split kernel   one wavefront per share: walks its slots with a wave-uniform cursor
+//                  (physical pages from the block table, one slot ahead) and a
+//                  three-page-deep register prefetch; whenever the (sequence, kv head)
+//                  changes it writes the online-softmax partial (running max, weight sum,
+//                  weighted value sum) of the g query heads that share the kv head
+//   merge kernel   per (sequence, kv head): log-sum-exp combination of the partials in
+//                  share order, normalisation, store
 // The partition depends on ctx_len only, the merge order is fixed: results are bitwise
 // reproducible and do not depend on the physical page order.
 //
