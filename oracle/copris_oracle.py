@@ -370,3 +370,125 @@ def grpo_surrogate(logp_cur, logp_buf, logp_roll, cu_seqlens, split, mask, adv, 
     obj_seq_mean = float(per_seq.sum() / B) if B > 0 else 0.0
     return {"surr": surr, "grad": grad, "seq_surr": seq_surr, "seq_cnt": seq_cnt,
             "obj_token_mean": obj_token_mean, "obj_seq_mean": obj_seq_mean}
+
+
+# --------------------------------------------------------------------------
+# Rollout management (Section 4): concurrency-controlled generation, early
+# termination, buffering of partial trajectories, prioritized resumption.
+# Host logic, integers only.  The model is replaced by given response lengths.
+# --------------------------------------------------------------------------
+def rollout_schedule(prompt_len, resp_len, pool, batch_inputs, page_size=16, max_stages=None):
+    """Token-by-token simulation of the rollout manager of Section 4.
+
+    prompt_len [I] and resp_len [I, N]: input i has N trajectories; trajectory (i, s)
+    stops after resp_len[i, s] >= 1 generated tokens.  `pool` is the fixed number of
+    concurrent requests N' ("Concurrency-Controlled Generation"), `batch_inputs` the
+    number B of inputs a training step needs ("Early Termination").
+
+    A rollout stage k = 0, 1, ... runs under one policy version:
+      * dispatch order: buffered unfinished trajectories first ("Prioritized
+        Resumption"), in (input, sample) order, then trajectories that have not
+        started, in (input, sample) order;
+      * the pool is filled to N' requests; each decode step every active request
+        generates one token, tagged with the stage (Eq. 6: the buffered log-probs of a
+        trajectory are the concatenation of its per-stage pieces, so a tag per token
+        is all the bookkeeping the concatenation needs); a request that reaches its
+        length finishes and its slot is refilled before the next step;
+      * after a step, if at least B inputs have all N trajectories finished, the stage
+        stops at once: the B complete inputs with the lowest indices form the training
+        batch and leave; running requests are paused and stay in the buffer with what
+        they have generated; finished trajectories of incomplete inputs stay too;
+      * a resumed trajectory is re-prefilled: prompt + tokens generated so far.
+    KV pages (page_size tokens each) are held by running requests only; they are
+    released when a request finishes or is paused (a new policy invalidates them).
+
+    The simulation ends when a stage cannot complete B inputs (inputs exhausted) or
+    after max_stages.  Returns a list of per-stage dicts:
+      steps              decode steps of the stage
+      generated          tokens generated in the stage
+      slot_steps_idle    pool slots x steps that had no request to run
+      batch_inputs       indices of the inputs consumed by the training step
+      batch_tokens       response tokens of the batch
+      batch_offpolicy    of which generated in an earlier stage (tag < k)
+      batch_traj_offpolicy  trajectories of the batch with at least one such token
+      max_staleness      max over batch tokens of (k - tag)
+      resumed            trajectories resumed at the start of the stage
+      reprefill_tokens   prompt + generated tokens re-prefilled for them
+      paused             unfinished trajectories left in the buffer at the end
+      buffered_complete  finished trajectories of incomplete inputs left in the buffer
+      peak_pages         most KV pages held at once during the stage
+    """
+    prompt_len = [int(x) for x in prompt_len]
+    resp = [[int(x) for x in row] for row in resp_len]
+    I = len(prompt_len)
+    N = len(resp[0]) if I else 0
+    gen = [[0] * N for _ in range(I)]            # tokens generated so far
+    tags = [[[] for _ in range(N)] for _ in range(I)]   # stage tag of every generated token
+    started = [[False] * N for _ in range(I)]
+    consumed = [False] * I
+    stages = []
+    k = 0
+
+    def pages(i, s):
+        return (prompt_len[i] + gen[i][s] + page_size - 1) // page_size
+
+    while max_stages is None or k < max_stages:
+        # dispatch queue of this stage
+        resume_q = [(i, s) for i in range(I) for s in range(N)
+                    if not consumed[i] and started[i][s] and gen[i][s] < resp[i][s]]
+        fresh_q = [(i, s) for i in range(I) for s in range(N) if not started[i][s]]
+        queue = resume_q + fresh_q
+        n_resume = len(resume_q)
+        qpos = 0
+        active = []
+        st = {"steps": 0, "generated": 0, "slot_steps_idle": 0, "resumed": 0, "reprefill_tokens": 0,
+              "peak_pages": 0}
+
+        def complete_inputs():
+            return [i for i in range(I) if not consumed[i]
+                    and all(started[i][s] and gen[i][s] >= resp[i][s] for s in range(N))]
+
+        done = None
+        if len(complete_inputs()) >= batch_inputs:
+            done = complete_inputs()          # enough inputs were already complete in the buffer
+        while done is None:
+            while len(active) < pool and qpos < len(queue):
+                i, s = queue[qpos]
+                if qpos < n_resume:
+                    st["resumed"] += 1
+                    st["reprefill_tokens"] += prompt_len[i] + gen[i][s]
+                qpos += 1
+                started[i][s] = True
+                active.append((i, s))
+            if not active:
+                break                           # nothing left to run: the stage cannot complete
+            # one decode step
+            st["steps"] += 1
+            st["slot_steps_idle"] += pool - len(active)
+            for i, s in active:
+                gen[i][s] += 1
+                tags[i][s].append(k)
+            st["generated"] += len(active)
+            st["peak_pages"] = max(st["peak_pages"], sum(pages(i, s) for i, s in active))
+            active = [(i, s) for i, s in active if gen[i][s] < resp[i][s]]
+            ci = complete_inputs()
+            if len(ci) >= batch_inputs:
+                done = ci
+        if done is None:
+            break
+        batch = done[:batch_inputs]
+        toks = [t for i in batch for s in range(N) for t in tags[i][s]]
+        st["batch_inputs"] = batch
+        st["batch_tokens"] = len(toks)
+        st["batch_offpolicy"] = sum(1 for t in toks if t < k)
+        st["batch_traj_offpolicy"] = sum(1 for i in batch for s in range(N) if any(t < k for t in tags[i][s]))
+        st["max_staleness"] = max((k - t for t in toks), default=0)
+        for i in batch:
+            consumed[i] = True
+        st["paused"] = sum(1 for i in range(I) for s in range(N)
+                           if not consumed[i] and started[i][s] and gen[i][s] < resp[i][s])
+        st["buffered_complete"] = sum(1 for i in range(I) for s in range(N)
+                                      if not consumed[i] and started[i][s] and gen[i][s] >= resp[i][s])
+        stages.append(st)
+        k += 1
+    return stages
