@@ -290,6 +290,26 @@ def main():
             "workload": f"{len(plens)} resumed trajectories, lengths {int(plens.min())}..{int(plens.max())}, "
                         f"{cfg.Hq}q/{cfg.Hkv}kv heads, causal, one layer"}
         del pd, pb
+    # ---- outside the step, host only: the rollout manager's schedule for 20 training steps
+    # at the paper's settings (Table 4: 64 inputs x 8 samples per step, pool 1024) ----
+    if args.config == 2:
+        rngs = np.random.default_rng(cfg.seed + 9)
+        n_in, n_s, n_b, n_pool, n_st = 64 * 40, 8, 64, 1024, 20
+        rl = np.minimum(np.maximum(np.rint(rngs.lognormal(7.5, 1.1, size=(n_in, n_s))), 1), 16384).astype(np.int32)
+        pl = np.full(n_in, cfg.prompt, dtype=np.int32)
+        t0s = time.perf_counter()
+        sched = binding.rollout_schedule(pl, rl, n_pool, n_b, max_stages=n_st)
+        t_sched = time.perf_counter() - t0s
+        bt = sum(x["batch_tokens"] for x in sched)
+        result["extras"]["rollout_schedule"] = {
+            "host_ms": round(t_sched * 1e3, 2), "stages": len(sched), "pool": n_pool,
+            "decode_steps": sum(x["steps"] for x in sched),
+            "offpolicy_token_frac": round(sum(x["batch_offpolicy"] for x in sched) / max(bt, 1), 4),
+            "reprefill_tokens_per_generated": round(sum(x["reprefill_tokens"] for x in sched)
+                                                    / max(sum(x["generated"] for x in sched), 1), 4),
+            "pool_idle_frac": round(sum(x["slot_steps_idle"] for x in sched)
+                                    / max(n_pool * sum(x["steps"] for x in sched), 1), 4),
+            "workload": f"{n_st} training steps of {n_b} inputs x {n_s} samples, response lengths of the config-2 recipe"}
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(cfg, inp, args.cpu_sample)
     print(json.dumps(result))

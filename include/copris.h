@@ -289,6 +289,48 @@ int copris_grpo_surrogate(const float* logp_cur, const float* logp_buf, const fl
                           float* surr, float* grad, float* seq_surr, int32_t* seq_cnt,
                           float* objective, int B, int64_t N, void* stream);
 
+/* ------------------------------------------------------------------------
+ * Rollout manager: the schedule of Section 4 for given response lengths.  HOST
+ * function: every pointer is host memory, nothing touches the GPU.
+ *
+ * "Concurrency-Controlled Generation": a fixed pool of `pool` (N') requests is kept
+ * in flight; a finished trajectory's slot is refilled at once.  "Early Termination": a
+ * stage stops as soon as `batch_inputs` (B) inputs have all of their `samples` (N)
+ * trajectories finished; the B complete inputs with the lowest indices leave as the
+ * training batch.  "Buffering of Partial Trajectories": running requests are paused
+ * and keep what they generated, with the stage each token was generated in (the
+ * per-stage pieces of Eq. 6); finished trajectories of incomplete inputs stay too.
+ * "Prioritized Resumption": the next stage dispatches the paused trajectories first,
+ * in (input, sample) order, then trajectories that have not started, in the same
+ * order; a resumed trajectory is re-prefilled (prompt + generated tokens).  One
+ * decode step gives every running request one token.  KV pages of page_size tokens
+ * are held by running requests only.
+ *
+ *   prompt_len [n_inputs] int32 >= 0      resp_len [n_inputs, samples] int32 >= 1
+ *   stats      [max_stages] out           batch_out [max_stages, batch_inputs] int32 out
+ *   n_stages   out: stages that completed a batch (the schedule ends when the inputs
+ *              cannot complete another one, or after max_stages)
+ * ------------------------------------------------------------------------ */
+typedef struct copris_stage_stats {
+  int64_t steps;                /* decode steps of the stage */
+  int64_t generated;            /* tokens generated in the stage */
+  int64_t slot_steps_idle;      /* pool slots x steps without a request to run */
+  int64_t batch_tokens;         /* response tokens of the training batch */
+  int64_t batch_offpolicy;      /* ... of which generated in an earlier stage */
+  int64_t batch_traj_offpolicy; /* trajectories of the batch with such tokens */
+  int64_t max_staleness;        /* max over batch tokens of (stage - stage generated in) */
+  int64_t resumed;              /* trajectories resumed in the stage */
+  int64_t reprefill_tokens;     /* prompt + generated tokens re-prefilled for them */
+  int64_t paused;               /* unfinished trajectories in the buffer at the end */
+  int64_t buffered_complete;    /* finished trajectories of incomplete inputs, likewise */
+  int64_t peak_pages;           /* most KV pages held at once */
+} copris_stage_stats;
+
+int copris_rollout_schedule(const int32_t* prompt_len, const int32_t* resp_len,
+                            int n_inputs, int samples, int pool, int batch_inputs,
+                            int page_size, int max_stages, copris_stage_stats* stats,
+                            int32_t* batch_out, int* n_stages);
+
 #ifdef __cplusplus
 }
 #endif

@@ -44,6 +44,18 @@ SIGNATURES = {
                               + [c_int, c_int64, c_void_p]),
 }
 
+
+
+class StageStats(ctypes.Structure):
+    """copris_stage_stats of include/copris.h."""
+    _fields_ = [(n, c_int64) for n in (
+        "steps", "generated", "slot_steps_idle", "batch_tokens", "batch_offpolicy",
+        "batch_traj_offpolicy", "max_staleness", "resumed", "reprefill_tokens", "paused",
+        "buffered_complete", "peak_pages")]
+
+
+SIGNATURES["copris_rollout_schedule"] = (c_int, [c_void_p, c_void_p] + [c_int] * 6 + [c_void_p] * 3)
+
 _lib = None
 
 
@@ -203,3 +215,28 @@ def prefill_attn(q, k, v, cu_seqlens, block_table, k_cache, v_cache, out, lse, *
         _ptr(out), _ptr(lse), B, T, Hq, Hkv, D, page_size, block_table.shape[1], num_pages,
         int(max_seqlen), float(scale), int(dtype), _stream(stream))
     _check(code, "copris_prefill_attn")
+
+
+def rollout_schedule(prompt_len, resp_len, pool: int, batch_inputs: int, page_size: int = 16,
+                     max_stages: Optional[int] = None) -> list:
+    """copris_rollout_schedule on host arrays (numpy); returns a list of per-stage dicts."""
+    import numpy as np
+    p = np.ascontiguousarray(prompt_len, dtype=np.int32)
+    r = np.ascontiguousarray(resp_len, dtype=np.int32)
+    n_inputs = int(p.size)
+    samples = int(r.shape[1]) if r.ndim == 2 and n_inputs else 1
+    if max_stages is None:
+        max_stages = n_inputs // max(int(batch_inputs), 1) + 1
+    stats = (StageStats * max(max_stages, 1))()
+    batch = np.zeros((max(max_stages, 1), max(int(batch_inputs), 1)), dtype=np.int32)
+    n = c_int(0)
+    code = load_library().copris_rollout_schedule(
+        p.ctypes.data, r.ctypes.data, n_inputs, samples, int(pool), int(batch_inputs), int(page_size),
+        int(max_stages), ctypes.addressof(stats), batch.ctypes.data, ctypes.addressof(n))
+    _check(code, "copris_rollout_schedule")
+    out = []
+    for k in range(n.value):
+        d = {name: int(getattr(stats[k], name)) for name, _ in StageStats._fields_}
+        d["batch_inputs"] = batch[k].tolist()
+        out.append(d)
+    return out

@@ -9,7 +9,7 @@ import sys
 PKG_DIR = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(PKG_DIR, "csrc")
 LIB_PATH = os.path.join(PKG_DIR, "libcopris.so")
-SOURCES = ["copris_api.hip", "decode_attn.hip", "prefill_attn.hip", "lmhead.hip", "is_ratio.hip"]
+SOURCES = ["copris_api.hip", "decode_attn.hip", "prefill_attn.hip", "lmhead.hip", "is_ratio.hip", "rollout_manager.cpp"]
 
 
 def hipcc_path() -> str:
