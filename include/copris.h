@@ -16,6 +16,17 @@
  *                          "Cross-stage Importance Sampling Correction", Eq. 8)
  *                          with the clip of Eq. 3 and masked per-sequence sums
  *
+ * and the steps around it:
+ *
+ *   copris_grpo_surrogate        the clipped surrogate of Eq. 3 on that ratio, its
+ *                                derivative and the aggregations of Eq. 2 / Table 4
+ *   copris_lmhead_token_logprob  log-probs of given tokens under the current policy
+ *                                (the recomputed side of Eq. 8), micro-batch sized
+ *   copris_prefill_attn          causal attention over resumed partial trajectories,
+ *                                refilling their KV pages (re-prefill, Section 5.3)
+ *   copris_rollout_schedule      the rollout manager of Section 4 for given response
+ *                                lengths (host function)
+ *
  * Conventions
  *   - Plain C.  Every pointer argument is a DEVICE pointer owned by the caller,
  *     unless stated otherwise.  The library allocates nothing, never
@@ -23,8 +34,8 @@
  *     kernels on `stream` (a hipStream_t passed as void*; NULL = the null
  *     stream) and returns.
  *   - Outputs are fully overwritten; inputs are never modified.  No global
- *     state: calls are re-entrant across streams given disjoint workspaces and
- *     outputs.
+ *     state besides the profiling hook: calls are re-entrant across streams given
+ *     disjoint workspaces and outputs.
  *   - Tensors are dense, row-major, last index fastest, and their base
  *     addresses must be 16-byte aligned.
  *   - dtype: COPRIS_F32 (0) or COPRIS_BF16 (1).  bf16 tensors accumulate in fp32.
