@@ -300,20 +300,18 @@ __device__ __forceinline__ void lm_given_block(const f32x16& acc, LmLaneState& s
 // Both operands reach LDS through LDS-direct loads (global_load_lds_dwordx4: each
 // lane's 16 bytes land at base + 16*lane, no registers in between), so the data in
 // flight lives in LDS rings:
-//   W       [128 rows][64 k] slabs of 16 KB, ring of kNW, issued kDW slabs ahead by
-//           waves 0-1 (HBM latency);
+//   W       [128 rows][64 k] slabs of 16 KB, ring of two, issued one slab ahead;
 //   hidden  [128 rows][64 k] units of 16 KB - the two batch halves of a slab are
-//           consumed one after the other against the same W slab - ring of 2, issued one
-//           unit ahead by waves 2-3 (L2 latency).
-// The roles are split by wave because the outstanding-load counter retires in order: a
-// wave that mixed the deep and the shallow stream would drain the deep one on every
-// unit.  The compiler cannot count LDS-direct loads per buffer (it would drain them all
-// before any LDS read), so the operand reads are inline ds_read_b128 and every wait is
-// explicit.  80 KB of LDS per workgroup: two workgroups fill a CU's 160 KB.
+//           consumed one after the other against the same W slab - ring of three,
+//           issued two units (one slab) ahead.
+// Every wave issues a quarter of each slab and unit.  The outstanding-load counter of a
+// wave retires in order, so the issue order is chosen such that what a wait needs is always
+// older than what may stay in flight: hidden(2d+2), W(d+1) at the top of slab d,
+// hidden(2d+3) at mid-slab.  The compiler cannot count LDS-direct loads per buffer (it
+// would drain them all before any LDS read), so the operand reads are inline ds_read_b128
+// and every wait is explicit.  80 KB of LDS per workgroup: two workgroups fill a CU's 160 KB.
 constexpr int kNW = 2;                              // W ring slabs
-constexpr int kDW = kNW - 1;                        // W prefetch distance (slabs)
 constexpr int kNH = 3;                              // hidden ring units
-constexpr int kDH = kNH - 1;                        // hidden prefetch distance (units)
 constexpr int kSlab = 128 * kMfBK * 2;              // 16 KB: a W slab or a hidden unit
 constexpr int kHRing = kNW * kSlab;                 // hidden ring starts here
 constexpr int kMfLds = kHRing + kNH * kSlab;        // 80 KB
@@ -363,57 +361,50 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   // ---- loader cursors (wave-uniform) ----
   const int my_tiles = blockIdx.x < n_tiles ? (n_tiles - 1 - blockIdx.x) / gridDim.x + 1 : 0;
   const int total = my_tiles * nkd;            // W slabs this workgroup consumes (hidden units: 2x)
-  const bool w_loader = wave < 2;
-  // LDS position P = 64*chunk + lane of a slab holds (row P>>3, stored granule P&7); the
-  // lane fetches the global granule that the swizzle maps there.  A loader wave moves
-  // chunks 8*(wave&1) .. +7 (rows 64*(wave&1) .. +63).
-  const int ld_row = 64 * (wave & 1) + (lane >> 3);          // + 8*j
-  // byte offset of the granule for row ld_row; for row ld_row + 8*j, (row>>1)&7 differs by
-  // 4*(j&1), i.e. the offset has bit 6 flipped for odd j
-  const uint32_t ld_g = ((lane & 7) ^ ((ld_row >> 1) & 7)) * 16;
-  int ld_n = 0;                                // W slabs (w_loader) / hidden units issued so far
-  int ld_tile = blockIdx.x, ld_kd = 0, ld_ring = 0, h_ring = 0;
+  // Every wave moves a quarter of every W slab and of every hidden unit: rows 32*wave ..
+  // 32*wave+31, four instructions of 8 rows x 128 bytes.  LDS position 64*chunk + lane of a
+  // slab holds (row 8*chunk + lane/8, stored granule lane%8); the lane fetches the global
+  // granule that the swizzle maps there: (row>>1)&7 = lane>>4 for even chunks, +4 for odd
+  // ones, i.e. bit 6 of the byte offset flips for odd j.
+  const int ld_row = 32 * wave + (lane >> 3);                // + 8*j
+  const uint32_t ld_g = ((lane & 7) ^ (lane >> 4)) * 16;
+  int w_n = 0, w_tile = blockIdx.x, w_kd = 0, w_ring = 0;    // W slabs issued so far, cursor, ring slot
+  int h_n = 0, h_kd = 0, h_ring = 0;                         // hidden units issued so far: (slab h_n>>1, half h_n&1)
   const char* wbase = reinterpret_cast<const char*>(weight);
   const char* hbase = reinterpret_cast<const char*>(hidden);
-  // Row offsets are recomputed at every issue (a few integer ops per 16 KB) rather than
-  // held in registers.  Rows past V re-read the last vocabulary row (masked in the
-  // epilogue); rows past C duplicate the last batch row (never used).
-  auto issue_w = [&]() __attribute__((always_inline)) {     // W slab number ld_n
-    char* dst = smem + ld_ring * kSlab + (8 * (wave & 1)) * 1024;
-    const uint32_t koff = static_cast<uint32_t>(ld_kd) * (kMfBK * 2) + ld_g;
-    const int vrow = ld_tile * kMfBM + ld_row;
+  // Rows past V re-read the last vocabulary row (masked in the epilogue); rows past C
+  // duplicate the last batch row (never used).
+  auto issue_w = [&]() __attribute__((always_inline)) {
+    char* dst = smem + w_ring * kSlab + (4 * wave) * 1024;
+    const uint32_t koff = static_cast<uint32_t>(w_kd) * (kMfBK * 2) + ld_g;
+    const int vrow = w_tile * kMfBM + ld_row;
 #pragma unroll
-    for (int j = 0; j < 8; ++j) {
+    for (int j = 0; j < 4; ++j) {
       const int v = min(vrow + 8 * j, V - 1);
       __builtin_amdgcn_global_load_lds(wbase + (static_cast<uint32_t>(v) * pitch + (koff ^ ((j & 1) * 64))),
                                        dst + j * 1024, 16, 0, 0);
     }
-    ld_ring = ld_ring + 1 == kNW ? 0 : ld_ring + 1;
-    ++ld_n;
-    if (++ld_kd == nkd) {
-      ld_kd = 0;
-      ld_tile += gridDim.x;
+    w_ring = w_ring + 1 == kNW ? 0 : w_ring + 1;
+    ++w_n;
+    if (++w_kd == nkd) {
+      w_kd = 0;
+      w_tile += gridDim.x;
     }
   };
-  auto issue_h = [&]() __attribute__((always_inline)) {     // hidden unit number ld_n: (slab ld_n>>1, half ld_n&1)
-    char* dst = smem + kHRing + h_ring * kSlab + (8 * (wave & 1)) * 1024;
+  auto issue_h = [&]() __attribute__((always_inline)) {
+    char* dst = smem + kHRing + h_ring * kSlab + (4 * wave) * 1024;
     h_ring = h_ring + 1 == kNH ? 0 : h_ring + 1;
-    const uint32_t koff = static_cast<uint32_t>(ld_kd) * (kMfBK * 2) + ld_g;
-    const int crow = c0 + 128 * (ld_n & 1) + ld_row;
+    const uint32_t koff = static_cast<uint32_t>(h_kd) * (kMfBK * 2) + ld_g;
+    const int crow = c0 + 128 * (h_n & 1) + ld_row;
 #pragma unroll
-    for (int j = 0; j < 8; ++j) {
+    for (int j = 0; j < 4; ++j) {
       const int c = min(crow + 8 * j, C - 1);
       __builtin_amdgcn_global_load_lds(hbase + (static_cast<uint32_t>(c) * pitch + (koff ^ ((j & 1) * 64))),
                                        dst + j * 1024, 16, 0, 0);
     }
-    if ((ld_n & 1) && ++ld_kd == nkd) ld_kd = 0;
-    ++ld_n;
+    if ((h_n & 1) && ++h_kd == nkd) h_kd = 0;
+    ++h_n;
   };
-  if (w_loader) {
-    for (int i = 0; i < kDW && ld_n < total; ++i) issue_w();
-  } else {
-    for (int i = 0; i < kDH && ld_n < 2 * total; ++i) issue_h();
-  }
 
   // this lane owns batch rows c0 + 128*half + 64*wq + 32*nt + l32 (state index 2*half + nt);
   // their stream keys stay in registers (a global load inside the tile loop would drain
@@ -435,6 +426,16 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     }
   }
 
+  // prologue.  A wave's loads complete in issue order, and that order is, per slab d:
+  // hidden(2d+2), W(d+1) at the top, hidden(2d+3) at mid-slab.  So at the top the wave may
+  // leave its newest four loads (hidden(2d+1)) in flight and knows W(d) and hidden(2d) have
+  // landed; at mid-slab it may leave eight (hidden(2d+2), W(d+1)) and knows hidden(2d+1) has.
+  if (total > 0) {
+    issue_h();
+    issue_w();
+    issue_h();
+  }
+
   int d_idx = 0, ring = 0, hring = 0;          // W slab being consumed (flat index), W / hidden ring slots
   for (int tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
     const int v0 = tile * kMfBM;
@@ -446,18 +447,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 
     for (int kd = 0; kd < nkd; ++kd, ++d_idx) {
       // ---- top: W slab d_idx and hidden unit (d_idx, half 0) have landed ----
-      if (w_loader && d_idx + kDW <= total) {
-        asm volatile("s_waitcnt vmcnt(%0)" ::"n"(8 * (kDW - 1)) : "memory");
-      } else if (!w_loader && 2 * d_idx + kDH <= 2 * total) {
-        asm volatile("s_waitcnt vmcnt(%0)" ::"n"(8 * (kDH - 1)) : "memory");
-      } else {
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-      }
+      asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
       asm volatile("s_barrier" ::: "memory");   // ... for every wave; all are done with slab d_idx-1
-      if (w_loader) {
-        if (ld_n < total) issue_w();
-      } else {
-        if (ld_n < 2 * total) issue_h();        // refills the slot of unit (d_idx-1, half 1)
+      if (d_idx + 1 < total) {
+        issue_h();                              // unit (d_idx+1, half 0) into the slot of (d_idx-1, half 1)
+        issue_w();                              // slab d_idx+1 into the slot of slab d_idx-1
       }
       const uint32_t wb = lds0 + ring * kSlab;
       ring = ring + 1 == kNW ? 0 : ring + 1;
@@ -471,15 +465,13 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
       for (int half = 0; half < 2; ++half) {
         if (half == 1) {
           // ---- middle: hidden unit (d_idx, half 1) has landed ----
-          if (!w_loader) {                                    // (W loaders keep their slabs in flight)
-            if (2 * d_idx + 1 + kDH <= 2 * total) {
-              asm volatile("s_waitcnt vmcnt(%0)" ::"n"(8 * (kDH - 1)) : "memory");
-            } else {
-              asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-            }
+          if (d_idx + 1 < total) {
+            asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+          } else {
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
           }
           asm volatile("s_barrier" ::: "memory");             // all are done with unit (d_idx, half 0)
-          if (!w_loader && ld_n < 2 * total) issue_h();       // refills that unit's slot
+          if (d_idx + 1 < total) issue_h();                   // unit (d_idx+1, half 1) into that slot
         }
         const uint32_t hb = lds0 + kHRing + hring * kSlab;
         hring = hring + 1 == kNH ? 0 : hring + 1;
