@@ -475,27 +475,40 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
         }
         const uint32_t hb = lds0 + kHRing + hring * kSlab;
         hring = hring + 1 == kNH ? 0 : hring + 1;
-        u32x4 b[2][2];
-        b[0][0] = lds_read128<0>(hb + b_off[0]);
-        b[0][1] = lds_read128<4096>(hb + b_off[0]);
-        if (half == 0) lds_wait_all(a);         // (also covers b[0])
+        // all eight hidden operands of the half at once, then sixteen products in two groups
+        // of eight: one wait per eight products instead of one per four
+        u32x4 b[4][2];
 #pragma unroll
         for (int k16 = 0; k16 < 4; ++k16) {
-          const int cur = k16 & 1, nxt = cur ^ 1;
-          if (k16 < 3) {
-            b[nxt][0] = lds_read128<0>(hb + b_off[k16 + 1]);
-            b[nxt][1] = lds_read128<4096>(hb + b_off[k16 + 1]);
-            lds_wait<2>(b[cur][0], b[cur][1]);
-          } else {
-            lds_wait<0>(b[cur][0], b[cur][1]);
+          if (half == 0 && k16 == 2) {
+            // (the wait counter holds 15: the W operands and the first four reads are
+            // retired before the last four are issued)
+            asm volatile("s_waitcnt lgkmcnt(0)"
+                         : "+v"(a[0][0]), "+v"(a[0][1]), "+v"(a[1][0]), "+v"(a[1][1]), "+v"(a[2][0]),
+                           "+v"(a[2][1]), "+v"(a[3][0]), "+v"(a[3][1]), "+v"(b[0][0]), "+v"(b[0][1]),
+                           "+v"(b[1][0]), "+v"(b[1][1])::"memory");
           }
-          const bf16x8 fb0 = __builtin_bit_cast(bf16x8, b[cur][0]);
-          const bf16x8 fb1 = __builtin_bit_cast(bf16x8, b[cur][1]);
+          b[k16][0] = lds_read128<0>(hb + b_off[k16]);
+          b[k16][1] = lds_read128<4096>(hb + b_off[k16]);
+        }
 #pragma unroll
-          for (int it = 0; it < 2; ++it) {
-            const bf16x8 fa = __builtin_bit_cast(bf16x8, a[k16][it]);
-            acc[half][it][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa, fb0, acc[half][it][0], 0, 0, 0);
-            acc[half][it][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa, fb1, acc[half][it][1], 0, 0, 0);
+        for (int grp = 0; grp < 2; ++grp) {
+          if (grp == 0 && half == 1) {
+            asm volatile("s_waitcnt lgkmcnt(4)" : "+v"(b[0][0]), "+v"(b[0][1]), "+v"(b[1][0]), "+v"(b[1][1])::"memory");
+          } else if (grp == 1) {
+            asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(b[2][0]), "+v"(b[2][1]), "+v"(b[3][0]), "+v"(b[3][1])::"memory");
+          }
+#pragma unroll
+          for (int kk = 0; kk < 2; ++kk) {
+            const int k16 = 2 * grp + kk;
+            const bf16x8 fb0 = __builtin_bit_cast(bf16x8, b[k16][0]);
+            const bf16x8 fb1 = __builtin_bit_cast(bf16x8, b[k16][1]);
+#pragma unroll
+            for (int it = 0; it < 2; ++it) {
+              const bf16x8 fa = __builtin_bit_cast(bf16x8, a[k16][it]);
+              acc[half][it][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa, fb0, acc[half][it][0], 0, 0, 0);
+              acc[half][it][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa, fb1, acc[half][it][1], 0, 0, 0);
+            }
           }
         }
       }
