@@ -32,7 +32,7 @@ def parse_args():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=50)
     ap.add_argument("--config", type=int, default=2, choices=[0, 1, 2],
                     help="decode config index (2 = the 7B-shaped C=256 config the metric is quoted on)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
