@@ -322,17 +322,8 @@ __device__ __forceinline__ u32x4 lds_read128(uint32_t addr) {
   asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(OFF) : "memory");
   return v;
 }
-// Waits until at most N LDS reads are outstanding; the operands that must have arrived
-// are tied so that no use can be scheduled above the wait.
-template <int N>
-__device__ __forceinline__ void lds_wait(u32x4& a, u32x4& b) {
-  asm volatile("s_waitcnt lgkmcnt(%2)" : "+v"(a), "+v"(b) : "n"(N) : "memory");
-}
-__device__ __forceinline__ void lds_wait_all(u32x4 (&a)[4][2]) {
-  asm volatile("s_waitcnt lgkmcnt(0)"
-               : "+v"(a[0][0]), "+v"(a[0][1]), "+v"(a[1][0]), "+v"(a[1][1]), "+v"(a[2][0]),
-                 "+v"(a[2][1]), "+v"(a[3][0]), "+v"(a[3][1])::"memory");
-}
+// (Waits on these reads are inline "s_waitcnt lgkmcnt(N)" statements that tie the operands
+// which must have arrived, so that no use can be scheduled above the wait.)
 
 template <bool GIVEN>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void lmhead_mfma_kernel(
