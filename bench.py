@@ -42,6 +42,8 @@ def parse_args():
                          "FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run)")
     ap.add_argument("--token-logprob-m", type=int, default=8192,
                     help="positions in the micro-batch of the given-token log-prob measurement")
+    ap.add_argument("--no-longtail", action="store_true",
+                    help="skip the decode-attention measurement on the long-tail stress configuration")
     ap.add_argument("--prefill-seqs", type=int, default=16,
                     help="resumed trajectories in the re-prefill attention measurement")
     return ap.parse_args()
@@ -290,6 +292,30 @@ def main():
             "workload": f"{len(plens)} resumed trajectories, lengths {int(plens.min())}..{int(plens.max())}, "
                         f"{cfg.Hq}q/{cfg.Hkv}kv heads, causal, one layer"}
         del pd, pb
+    # ---- outside the step: decode attention on the long-tail stress configuration (resumed
+    # 32k-token trajectories among short ones: what the split along the context is for) ----
+    if args.config == 2 and not args.no_longtail:
+        cfg3 = W.DECODE_CONFIGS[3]
+        inp3 = W.make_decode_inputs(cfg3, with_lmhead=False)
+        a3 = runner.stage_attn(inp3, cfg3.dtype, dev)
+        for _ in range(5):
+            a3.run(stream)
+        torch.cuda.synchronize()
+        l0e, l1e = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        l0e.record(stream)
+        for _ in range(args.steps):
+            a3.run(stream)
+        l1e.record(stream)
+        torch.cuda.synchronize()
+        lt_ms = l0e.elapsed_time(l1e) / args.steps
+        ctx3 = inp3["ctx_len"].astype(np.int64)
+        kv3 = int(ctx3.sum()) * 2 * cfg3.Hkv * cfg3.D * cfg3.elem_bytes
+        result["extras"]["decode_attn_longtail"] = {
+            "call_ms": round(lt_ms, 4), "kv_bytes": kv3, "achieved_GBps": round(kv3 / (lt_ms * 1e-3) / 1e9, 1),
+            "frac_hbm": round(kv3 / (lt_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+            "workload": f"config 3 ({cfg3.name}): C={cfg3.C}, ctx {int(ctx3.min())}..{int(ctx3.max())}, "
+                        f"{int((ctx3 == ctx3.max()).sum())} sequences at the maximum"}
+        del a3, inp3
     # ---- outside the step, host only: the rollout manager's schedule for 20 training steps
     # at the paper's settings (Table 4: 64 inputs x 8 samples per step, pool 1024) ----
     if args.config == 2:
