@@ -37,6 +37,7 @@ constexpr int kTileQ = 32;                        // query tokens per workgroup
 constexpr int kStepGranules = kP * kD * 2 / 16;   // 256 16-byte granules of K (and of V) per step
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
+constexpr float kSlack = 6.0f;   // scores may exceed the softmax reference by 2^kSlack
 
 __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
   uint32_t r;
@@ -202,26 +203,40 @@ __global__ __launch_bounds__(PrefillThreads<G>::value) void prefill_attn_kernel(
           }
         }
       }
-      float alpha[2];
+      // The running reference m of a query only has to keep the weights in range, so it is
+      // left alone while no score of the step exceeds it by more than kSlack (in log2 units):
+      // the step then needs no exchange between lanes and no rescaling of the state.
+      float loc[2];
+  #pragma unroll
+      for (int nb = 0; nb < 2; ++nb)
+        loc[nb] = fmaxf(fmaxf(t[nb][0], t[nb][1]), fmaxf(t[nb][2], t[nb][3]));
+      const bool grow = loc[0] > m_run[0] + kSlack || loc[1] > m_run[1] + kSlack;
       s16x4 pf[2];
+      if (__builtin_amdgcn_ballot_w64(grow) != 0) {
+        float alpha[2];
   #pragma unroll
-      for (int nb = 0; nb < 2; ++nb) {
-        float mx = fmaxf(fmaxf(t[nb][0], t[nb][1]), fmaxf(t[nb][2], t[nb][3]));
-        mx = fmaxf(mx, __shfl_xor(mx, 16, kWave));
-        mx = fmaxf(mx, __shfl_xor(mx, 32, kWave));
-        const float m_new = fmaxf(m_run[nb], mx);
-        alpha[nb] = __builtin_amdgcn_exp2f(m_run[nb] - m_new);
-        m_run[nb] = m_new;
-        float p[4];
-  #pragma unroll
-        for (int rr = 0; rr < 4; ++rr) p[rr] = __builtin_amdgcn_exp2f(t[nb][rr] - m_new);
-        l_run[nb] = l_run[nb] * alpha[nb] + ((p[0] + p[1]) + (p[2] + p[3]));
-        const uint2 pk = make_uint2(pack_bf16x2(p[0], p[1]), pack_bf16x2(p[2], p[3]));
-        pf[nb] = __builtin_bit_cast(s16x4, pk);
-      }
-      if (__builtin_amdgcn_ballot_w64(alpha[0] != 1.0f || alpha[1] != 1.0f) != 0) {
+        for (int nb = 0; nb < 2; ++nb) {
+          float mx = loc[nb];
+          mx = fmaxf(mx, __shfl_xor(mx, 16, kWave));
+          mx = fmaxf(mx, __shfl_xor(mx, 32, kWave));
+          // only a query whose own scores outgrew its reference moves it, so a query's
+          // arithmetic does not depend on the other queries of the wave
+          const float m_new = (mx > m_run[nb] + kSlack) ? mx : m_run[nb];
+          alpha[nb] = __builtin_amdgcn_exp2f(m_run[nb] - m_new);
+          m_run[nb] = m_new;
+          l_run[nb] *= alpha[nb];
+        }
   #pragma unroll
         for (int i = 0; i < 16; ++i) o[i >> 3][i & 7] *= alpha[i >> 3];
+      }
+  #pragma unroll
+      for (int nb = 0; nb < 2; ++nb) {
+        float p[4];
+  #pragma unroll
+        for (int rr = 0; rr < 4; ++rr) p[rr] = __builtin_amdgcn_exp2f(t[nb][rr] - m_run[nb]);
+        l_run[nb] += (p[0] + p[1]) + (p[2] + p[3]);
+        const uint2 pk = make_uint2(pack_bf16x2(p[0], p[1]), pack_bf16x2(p[2], p[3]));
+        pf[nb] = __builtin_bit_cast(s16x4, pk);
       }
   #pragma unroll
       for (int dt = 0; dt < 8; ++dt) {
