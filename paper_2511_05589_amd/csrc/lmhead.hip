@@ -304,10 +304,11 @@ __device__ __forceinline__ void lm_given_block(const f32x16& acc, LmLaneState& s
 //   hidden  [128 rows][64 k] units of 16 KB - the two batch halves of a slab are
 //           consumed one after the other against the same W slab - ring of three,
 //           issued two units (one slab) ahead.
-// Every wave issues a quarter of each slab and unit.  The outstanding-load counter of a
-// wave retires in order, so the issue order is chosen such that what a wait needs is always
-// older than what may stay in flight: hidden(2d+2), W(d+1) at the top of slab d,
-// hidden(2d+3) at mid-slab.  The compiler cannot count LDS-direct loads per buffer (it
+// Every wave issues a quarter of each slab and unit, one load at a time between the matrix
+// products.  The outstanding-load counter of a wave retires in order, so the issue order is
+// chosen such that what a wait needs is always older than what may stay in flight: per slab
+// d hidden(2d+2), W(d+1) - the last two of its four loads after the middle barrier - then
+// hidden(2d+3).  The compiler cannot count LDS-direct loads per buffer (it
 // would drain them all before any LDS read), so the operand reads are inline ds_read_b128
 // and every wait is explicit.  80 KB of LDS per workgroup: two workgroups fill a CU's 160 KB.
 constexpr int kNW = 2;                              // W ring slabs
@@ -359,42 +360,48 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   // ones, i.e. bit 6 of the byte offset flips for odd j.
   const int ld_row = 32 * wave + (lane >> 3);                // + 8*j
   const uint32_t ld_g = ((lane & 7) ^ (lane >> 4)) * 16;
-  int w_n = 0, w_tile = blockIdx.x, w_kd = 0, w_ring = 0;    // W slabs issued so far, cursor, ring slot
-  int h_n = 0, h_kd = 0, h_ring = 0;                         // hidden units issued so far: (slab h_n>>1, half h_n&1)
+  int w_tile = blockIdx.x, w_kd = 0, w_ring = 0;             // W cursor (tile, slab) and ring slot
+  int h_n = 0, h_kd = 0, h_ring = 0;                         // hidden units issued so far (half = h_n & 1), slab, slot
   const char* wbase = reinterpret_cast<const char*>(weight);
   const char* hbase = reinterpret_cast<const char*>(hidden);
   // Rows past V re-read the last vocabulary row (masked in the epilogue); rows past C
   // duplicate the last batch row (never used).
-  auto issue_w = [&]() __attribute__((always_inline)) {
-    char* dst = smem + w_ring * kSlab + (4 * wave) * 1024;
+  // one of the four loads of this wave's quarter of the W slab / hidden unit at the cursor
+  auto w_load = [&](int j) __attribute__((always_inline)) {
+    char* dst = smem + w_ring * kSlab + (4 * wave + j) * 1024;
     const uint32_t koff = static_cast<uint32_t>(w_kd) * (kMfBK * 2) + ld_g;
-    const int vrow = w_tile * kMfBM + ld_row;
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const int v = min(vrow + 8 * j, V - 1);
-      __builtin_amdgcn_global_load_lds(wbase + (static_cast<uint32_t>(v) * pitch + (koff ^ ((j & 1) * 64))),
-                                       dst + j * 1024, 16, 0, 0);
-    }
+    const int v = min(w_tile * kMfBM + ld_row + 8 * j, V - 1);
+    __builtin_amdgcn_global_load_lds(wbase + (static_cast<uint32_t>(v) * pitch + (koff ^ ((j & 1) * 64))), dst,
+                                     16, 0, 0);
+  };
+  auto w_advance = [&]() __attribute__((always_inline)) {
     w_ring = w_ring + 1 == kNW ? 0 : w_ring + 1;
-    ++w_n;
     if (++w_kd == nkd) {
       w_kd = 0;
       w_tile += gridDim.x;
     }
   };
-  auto issue_h = [&]() __attribute__((always_inline)) {
-    char* dst = smem + kHRing + h_ring * kSlab + (4 * wave) * 1024;
-    h_ring = h_ring + 1 == kNH ? 0 : h_ring + 1;
+  auto h_load = [&](int j) __attribute__((always_inline)) {
+    char* dst = smem + kHRing + h_ring * kSlab + (4 * wave + j) * 1024;
     const uint32_t koff = static_cast<uint32_t>(h_kd) * (kMfBK * 2) + ld_g;
-    const int crow = c0 + 128 * (h_n & 1) + ld_row;
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const int c = min(crow + 8 * j, C - 1);
-      __builtin_amdgcn_global_load_lds(hbase + (static_cast<uint32_t>(c) * pitch + (koff ^ ((j & 1) * 64))),
-                                       dst + j * 1024, 16, 0, 0);
-    }
+    const int c = min(c0 + 128 * (h_n & 1) + ld_row + 8 * j, C - 1);
+    __builtin_amdgcn_global_load_lds(hbase + (static_cast<uint32_t>(c) * pitch + (koff ^ ((j & 1) * 64))), dst,
+                                     16, 0, 0);
+  };
+  auto h_advance = [&]() __attribute__((always_inline)) {
+    h_ring = h_ring + 1 == kNH ? 0 : h_ring + 1;
     if ((h_n & 1) && ++h_kd == nkd) h_kd = 0;
     ++h_n;
+  };
+  auto issue_w = [&]() __attribute__((always_inline)) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) w_load(j);
+    w_advance();
+  };
+  auto issue_h = [&]() __attribute__((always_inline)) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) h_load(j);
+    h_advance();
   };
 
   // this lane owns batch rows c0 + 128*half + 64*wq + 32*nt + l32 (state index 2*half + nt);
@@ -418,9 +425,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   }
 
   // prologue.  A wave's loads complete in issue order, and that order is, per slab d:
-  // hidden(2d+2), W(d+1) at the top, hidden(2d+3) at mid-slab.  So at the top the wave may
-  // leave its newest four loads (hidden(2d+1)) in flight and knows W(d) and hidden(2d) have
-  // landed; at mid-slab it may leave eight (hidden(2d+2), W(d+1)) and knows hidden(2d+1) has.
+  // hidden(2d+2) and half of W(d+1) before the middle barrier, the rest of W(d+1) and
+  // hidden(2d+3) after it.  So at the top the wave may leave its newest four loads
+  // (hidden(2d+1)) in flight and knows W(d) and hidden(2d) have landed; at mid-slab it may
+  // leave the six issued since the top and knows hidden(2d+1) has.
   if (total > 0) {
     issue_h();
     issue_w();
@@ -440,10 +448,6 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
       // ---- top: W slab d_idx and hidden unit (d_idx, half 0) have landed ----
       asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
       asm volatile("s_barrier" ::: "memory");   // ... for every wave; all are done with slab d_idx-1
-      if (d_idx + 1 < total) {
-        issue_h();                              // unit (d_idx+1, half 0) into the slot of (d_idx-1, half 1)
-        issue_w();                              // slab d_idx+1 into the slot of slab d_idx-1
-      }
       const uint32_t wb = lds0 + ring * kSlab;
       ring = ring + 1 == kNW ? 0 : ring + 1;
       u32x4 a[4][2];
@@ -455,14 +459,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 #pragma unroll
       for (int half = 0; half < 2; ++half) {
         if (half == 1) {
-          // ---- middle: hidden unit (d_idx, half 1) has landed ----
-          if (d_idx + 1 < total) {
-            asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
-          } else {
-            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-          }
+          // ---- middle: hidden unit (d_idx, half 1) has landed (the six loads issued since
+          // the top may stay in flight) ----
+          asm volatile("s_waitcnt vmcnt(6)" ::: "memory");
           asm volatile("s_barrier" ::: "memory");             // all are done with unit (d_idx, half 0)
-          if (d_idx + 1 < total) issue_h();                   // unit (d_idx+1, half 1) into that slot
         }
         const uint32_t hb = lds0 + kHRing + hring * kSlab;
         hring = hring + 1 == kNH ? 0 : hring + 1;
@@ -490,15 +490,33 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
             asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(b[2][0]), "+v"(b[2][1]), "+v"(b[3][0]), "+v"(b[3][1])::"memory");
           }
 #pragma unroll
-          for (int kk = 0; kk < 2; ++kk) {
-            const int k16 = 2 * grp + kk;
-            const bf16x8 fb0 = __builtin_bit_cast(bf16x8, b[k16][0]);
-            const bf16x8 fb1 = __builtin_bit_cast(bf16x8, b[k16][1]);
-#pragma unroll
-            for (int it = 0; it < 2; ++it) {
-              const bf16x8 fa = __builtin_bit_cast(bf16x8, a[k16][it]);
-              acc[half][it][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa, fb0, acc[half][it][0], 0, 0, 0);
-              acc[half][it][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa, fb1, acc[half][it][1], 0, 0, 0);
+          for (int m = 0; m < 8; ++m) {
+            const int k16 = 2 * grp + (m >> 2), it = (m >> 1) & 1;
+            const bf16x8 fa = __builtin_bit_cast(bf16x8, a[k16][it]);
+            const bf16x8 fb = __builtin_bit_cast(bf16x8, b[k16][m & 1]);
+            acc[half][it][m & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa, fb, acc[half][it][m & 1], 0, 0, 0);
+            // The twelve loads a wave issues per slab go out one at a time between the
+            // products (three per group of eight).  Issued in a bunch they keep every wave
+            // of the CU at the issue stage while the address unit works through them, and the
+            // matrix pipes idle meanwhile; spread out they cost the products nothing.
+            // Order: hidden (d+1, half 0), W slab d+1 (its slot and that unit's are free since
+            // the top barrier), then hidden (d+1, half 1) after the middle barrier has freed
+            // the slot of (d, half 0).  Past the last slab the loads re-read clamped rows into
+            // ring slots nobody reads any more.
+            if (m == 1 || m == 4 || m == 6) {
+              const int q = 3 * (2 * half + grp) + (m == 1 ? 0 : m == 4 ? 1 : 2);   // 0 .. 11
+              __builtin_amdgcn_sched_barrier(0);
+              if (q < 4) {
+                h_load(q);
+                if (q == 3) h_advance();
+              } else if (q < 8) {
+                w_load(q - 4);
+                if (q == 7) w_advance();
+              } else {
+                h_load(q - 8);
+                if (q == 11) h_advance();
+              }
+              __builtin_amdgcn_sched_barrier(0);
             }
           }
         }
