@@ -5,16 +5,20 @@
 //
 // bf16, head_dim 128, page 16.  One workgroup owns (sequence, kv head, tile of 32 query
 // tokens); wave h of it owns query head kvh*g + h for those 32 tokens, as two blocks of 16
-// queries.  The workgroup walks the sequence's K/V in 16-token steps up to the tile's own
-// tokens; a step's K and V rows (2 x 4 KB) are fetched once by all waves together,
-// register-staged one step ahead, parked in a double-buffered LDS tile and read by every
-// wave in operand layout.  The products are those of the decode kernel with the 16 queries
-// of a block in place of the 16-padded head group:
-//     S^T[token][query] = K[token][:] . Q[query][:]           4 x mfma 16x16x32
-//     O^T[d][query]    += V^T[d][token] . P^T[token][query]   8 x mfma 16x16x16
-// so the K and V operands are read from LDS once per step and used for both query blocks,
-// and max / sum / rescale of a query live in the lane that owns it.  Only the one or two
-// steps on the diagonal need the causal mask.  The workgroup that owns a tile also writes
+// queries.  The workgroup walks the sequence's K/V in 32-token steps (two pages) up to the
+// tile's own tokens, which are the last step; a step's K and V rows (2 x 8 KB) are fetched
+// once by all waves together, register-staged two steps ahead, parked in a double-buffered
+// LDS tile and read by every wave in operand layout.  Per block of 16 queries:
+//     S^T[token][query] = K[token][:] . Q[query][:]           2 x 4 x mfma 16x16x32 (16 tokens each)
+//     O^T[d][query]    += V^T[d][token] . P^T[token][query]   8 x mfma 16x16x32 (all 32 tokens)
+// The value product runs over the step's 32 tokens at once (the 32-deep instruction has
+// twice the rate of the 16-deep one): its k-slot (g, e) is token 4g+e of the first page for
+// e < 4 and token 4g+e-4 of the second page for e >= 4, which is exactly how the two score
+// tiles leave the weights in a lane and how the transposing LDS read delivers V - both
+// operands are two register pairs put side by side, nothing moves between lanes.
+// The K and V operands are read from LDS once per step and used for both query blocks,
+// and max / sum / rescale of a query live in the lane that owns it.  Only the last step
+// needs the causal mask.  The workgroup that owns a tile also writes
 // that tile's K/V rows to the sequence's pages (each row is written by exactly one
 // workgroup).  Tiles are taken from the end of the sequences first (the long ones).
 #include <type_traits>
@@ -26,6 +30,7 @@ namespace copris {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef short s16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
@@ -34,7 +39,10 @@ namespace {
 constexpr int kD = 128;
 constexpr int kP = 16;
 constexpr int kTileQ = 32;                        // query tokens per workgroup
-constexpr int kStepGranules = kP * kD * 2 / 16;   // 256 16-byte granules of K (and of V) per step
+constexpr int kPageGranules = kP * kD * 2 / 16;   // 256 16-byte granules of K (and of V) per page
+constexpr int kSubs = 2;                          // pages per step
+constexpr int kStepTok = kSubs * kP;              // 32 tokens per step (= kTileQ: a tile's own tokens are one step)
+constexpr int kStepGranules = kSubs * kPageGranules;   // 512 granules of K (and of V) per step
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 constexpr float kSlack = 6.0f;   // scores may exceed the softmax reference by 2^kSlack
@@ -50,10 +58,10 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
 __device__ __forceinline__ int swz_k(int row, int c) { return row * 16 + (c ^ (row & 15)); }
 __device__ __forceinline__ int swz_v(int row, int c) { return row * 16 + (c ^ ((row & 7) << 1)); }
 
-// Threads of a workgroup: G waves where that divides the 512 granules of a step evenly,
-// else eight waves of which the first G compute and all fetch.
+// Threads of a workgroup: four or eight waves (they divide the 1024 granules of a step
+// evenly and keep the staging registers few); the first G compute, all fetch.
 template <int G> struct PrefillThreads {
-  static constexpr int value = (8 % G == 0) ? 64 * G : 512;
+  static constexpr int value = G <= 4 ? 256 : 512;
 };
 
 template <int G>
@@ -81,7 +89,8 @@ __global__ __launch_bounds__(PrefillThreads<G>::value) void prefill_attn_kernel(
   const bool computes = wave < G;                 // (the other waves only move data)
   const int head = kvh * G + min(wave, G - 1);
   const int q0 = tile * kTileQ;                      // first query token of the tile
-  const int last_step = min(2 * tile + 1, (len - 1) / kP);
+  const int last_step = tile;                        // the tile's own tokens
+  const int last_page = (len - 1) / kP;
   const int32_t* bt = block_table + static_cast<size_t>(b) * max_pages;
 
   // Q^T operands: lane (n, bq) holds Q[query n of block nb][32*kk + 8*bq .. +8]; queries past
@@ -100,8 +109,8 @@ __global__ __launch_bounds__(PrefillThreads<G>::value) void prefill_attn_kernel(
     }
   }
 
-  // ---- cooperative, register-staged fetch of one step (16 tokens of K and of V) ----
-  // granule i of a step: i < 256 is K, else V; token (i & 255) >> 4, column granule i & 15.
+  // ---- cooperative, register-staged fetch of one step (32 tokens of K and of V) ----
+  // granule i of a step: i < 512 is K, else V; token (i & 511) >> 4, column granule i & 15.
   // Rows past the end of the sequence re-read its last row (they are masked below).
   // two register stages: the fetch of step s+2 is in flight while step s+1 is parked
   u32x4 stage_a[kStage], stage_b[kStage];
@@ -110,27 +119,31 @@ __global__ __launch_bounds__(PrefillThreads<G>::value) void prefill_attn_kernel(
 #pragma unroll
     for (int j = 0; j < kStage; ++j) {
       const int i = tid + j * kThreads;
-      const int tok = min(step * kP + ((i & 255) >> 4), len - 1);
+      const int tok = min(step * kStepTok + ((i & (kStepGranules - 1)) >> 4), len - 1);
       const size_t g = (static_cast<size_t>(s0 + tok) * Hkv + kvh) * (kD * 2 / 16) + (i & 15);
       const u32x4* src = (i < kStepGranules) ? k : v;
       stage[j] = src[g];
     }
   };
-  // park the staged step in LDS buffer `buf`; a step of the tile's own tokens also goes to
-  // the sequence's page (slots past the end of the sequence are left alone)
+  // park the staged step in LDS buffer `buf` (page-sized halves, each swizzled on its own);
+  // the step of the tile's own tokens also goes to the sequence's pages (slots past the end
+  // of the sequence are left alone)
   auto park = [&](u32x4 (&stage)[kStage], int step, int buf, auto may_own) __attribute__((always_inline)) {
-    const bool own = decltype(may_own)::value && step >= 2 * tile;
-    const size_t page = own ? (static_cast<size_t>(bt[step]) * Hkv + kvh) * kStepGranules : 0;
+    const bool own = decltype(may_own)::value && step == tile;
 #pragma unroll
     for (int j = 0; j < kStage; ++j) {
       const int i = tid + j * kThreads;
-      const int gi = i & 255, tok = gi >> 4, c = gi & 15;
+      const int gi = i & (kStepGranules - 1), sub = gi >> 8, tok = (gi >> 4) & 15, c = gi & 15;
+      const bool live = own && step * kStepTok + sub * kP + tok < len;
+      // (the table entry of a page past the sequence's last one is never read)
+      const size_t page =
+          own ? (static_cast<size_t>(bt[min(kSubs * step + sub, last_page)]) * Hkv + kvh) * kPageGranules : 0;
       if (i < kStepGranules) {
-        lds_k[buf][swz_k(tok, c)] = stage[j];
-        if (own && step * kP + tok < len) k_cache[page + gi] = stage[j];
+        lds_k[buf][sub * kPageGranules + swz_k(tok, c)] = stage[j];
+        if (live) k_cache[page + (gi & (kPageGranules - 1))] = stage[j];
       } else {
-        lds_v[buf][swz_v(tok, c)] = stage[j];
-        if (own && step * kP + tok < len) v_cache[page + gi] = stage[j];
+        lds_v[buf][sub * kPageGranules + swz_v(tok, c)] = stage[j];
+        if (live) v_cache[page + (gi & (kPageGranules - 1))] = stage[j];
       }
     }
   };
@@ -147,74 +160,66 @@ __global__ __launch_bounds__(PrefillThreads<G>::value) void prefill_attn_kernel(
 
   // one step; `cur` holds the rows of step+1 (fetched a step ago), `nxt` is free and takes
   // the fetch of step+2 (unconditional: a fetch past the end stays in bounds and is dropped)
-  // diag = false: a step strictly before the tile's own tokens (no mask, no page write, and
-  // the step after it exists)
+  // diag = false: a step strictly before the tile's own tokens whose successor is not the
+  // tile's own step either (no mask, no page write, and the step after it exists)
   auto do_step = [&](u32x4 (&cur)[kStage], u32x4 (&nxt)[kStage], const int step, auto diag) __attribute__((always_inline)) {
     constexpr bool kDiag = decltype(diag)::value;
     const int buf = step & 1;
     fetch(nxt, step + 2);
 
     if (computes) {
-      // K rows as the A operand of the score product (token = lane & 15), read once for both
-      // query blocks
-      bf16x8 kf[4];
-  #pragma unroll
-      for (int kk = 0; kk < 4; ++kk)
-        kf[kk] = __builtin_bit_cast(bf16x8, lds_k[buf][swz_k(n, 4 * kk + bq)]);
-      // V^T as the A operand of the value product through the transposing read (lane supplies
-      // row 4*bq + n/4, columns 16*dt + 4*(n%4) .. +3)
-      s16x4 vf[8];
-      {
-        const int vrow = 4 * bq + (n >> 2);
-        const char* vbase = reinterpret_cast<const char*>(lds_v[buf]) + (n & 1) * 8;
-  #pragma unroll
-        for (int dt = 0; dt < 8; ++dt) {
-          const char* addr = vbase + swz_v(vrow, 2 * dt + ((n & 3) >> 1)) * 16;
-          vf[dt] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(addr));
-        }
-      }
-      const bool tail = kDiag && step * kP + kP > len;  // tokens past the end of the sequence
-      // Both query blocks go through every stage together (two independent dependency chains
-      // for the scheduler to interleave).  A block whose queries all lie before the step's
-      // tokens is fully masked: its weights are exp2(-inf - m) = 0 and its state is unchanged
-      // (m is finite from step 0 on: token 0 is visible to every query).
-      f32x4 sc[2];
-  #pragma unroll
-      for (int nb = 0; nb < 2; ++nb) {
-        sc[nb] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
-  #pragma unroll
+      const bool tail = kDiag && step * kStepTok + kStepTok > len;  // tokens past the end of the sequence
+      // Scores of the two pages: K rows as the A operand (token = lane & 15), read once for
+      // both query blocks.  This lane: query n of each block, tokens 4*bq .. 4*bq+3 of each page.
+      // A block whose queries all lie before a page's tokens is fully masked there: its
+      // weights are exp2(-inf - m) = 0 (m is finite from step 0 on: token 0 is visible to
+      // every query).
+      float t[kSubs][2][4];
+#pragma unroll
+      for (int sub = 0; sub < kSubs; ++sub) {
+        if (sub > 0) __builtin_amdgcn_sched_barrier(0);   // (one page's K operands in registers at a time)
+        bf16x8 kf[4];
+#pragma unroll
         for (int kk = 0; kk < 4; ++kk)
-          sc[nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[kk], qf[nb][kk], sc[nb], 0, 0, 0);
-      }
-      // this lane: query n of each block, tokens 4*bq .. 4*bq+3 of the step
-      float t[2][4];
-  #pragma unroll
-      for (int nb = 0; nb < 2; ++nb)
-  #pragma unroll
-        for (int rr = 0; rr < 4; ++rr) t[nb][rr] = sc[nb][rr] * scale_log2e;
-      if (kDiag && (step >= 2 * tile || tail)) {       // a step on the diagonal or at the end
-  #pragma unroll
+          kf[kk] = __builtin_bit_cast(bf16x8, lds_k[buf][sub * kPageGranules + swz_k(n, 4 * kk + bq)]);
+#pragma unroll
         for (int nb = 0; nb < 2; ++nb) {
-          const int tq = q0 + 16 * nb + n;
-  #pragma unroll
-          for (int rr = 0; rr < 4; ++rr) {
-            const int tk = step * kP + 4 * bq + rr;
-            t[nb][rr] = (tk <= tq && tk < len) ? t[nb][rr] : -INFINITY;
-          }
+          f32x4 sc = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+          for (int kk = 0; kk < 4; ++kk)
+            sc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[kk], qf[nb][kk], sc, 0, 0, 0);
+#pragma unroll
+          for (int rr = 0; rr < 4; ++rr) t[sub][nb][rr] = sc[rr] * scale_log2e;
         }
+      }
+      if (kDiag && (step == tile || tail)) {           // the tile's own step, or one at the end
+#pragma unroll
+        for (int sub = 0; sub < kSubs; ++sub)
+#pragma unroll
+          for (int nb = 0; nb < 2; ++nb) {
+            const int tq = q0 + 16 * nb + n;
+#pragma unroll
+            for (int rr = 0; rr < 4; ++rr) {
+              const int tk = step * kStepTok + sub * kP + 4 * bq + rr;
+              t[sub][nb][rr] = (tk <= tq && tk < len) ? t[sub][nb][rr] : -INFINITY;
+            }
+          }
       }
       // The running reference m of a query only has to keep the weights in range, so it is
       // left alone while no score of the step exceeds it by more than kSlack (in log2 units):
       // the step then needs no exchange between lanes and no rescaling of the state.
       float loc[2];
-  #pragma unroll
-      for (int nb = 0; nb < 2; ++nb)
-        loc[nb] = fmaxf(fmaxf(t[nb][0], t[nb][1]), fmaxf(t[nb][2], t[nb][3]));
+#pragma unroll
+      for (int nb = 0; nb < 2; ++nb) {
+        loc[nb] = fmaxf(fmaxf(t[0][nb][0], t[0][nb][1]), fmaxf(t[0][nb][2], t[0][nb][3]));
+#pragma unroll
+        for (int sub = 1; sub < kSubs; ++sub)
+          loc[nb] = fmaxf(loc[nb], fmaxf(fmaxf(t[sub][nb][0], t[sub][nb][1]), fmaxf(t[sub][nb][2], t[sub][nb][3])));
+      }
       const bool grow = loc[0] > m_run[0] + kSlack || loc[1] > m_run[1] + kSlack;
-      s16x4 pf[2];
       if (__builtin_amdgcn_ballot_w64(grow) != 0) {
         float alpha[2];
-  #pragma unroll
+#pragma unroll
         for (int nb = 0; nb < 2; ++nb) {
           float mx = loc[nb];
           mx = fmaxf(mx, __shfl_xor(mx, 16, kWave));
@@ -226,22 +231,45 @@ __global__ __launch_bounds__(PrefillThreads<G>::value) void prefill_attn_kernel(
           m_run[nb] = m_new;
           l_run[nb] *= alpha[nb];
         }
-  #pragma unroll
+#pragma unroll
         for (int i = 0; i < 16; ++i) o[i >> 3][i & 7] *= alpha[i >> 3];
       }
-  #pragma unroll
+      // weights of the step's 32 tokens as the B operand of the 32-deep value product:
+      // the first page's four in k-slots 0..3, the second page's in 4..7
+      bf16x8 pf[2];
+#pragma unroll
       for (int nb = 0; nb < 2; ++nb) {
-        float p[4];
-  #pragma unroll
-        for (int rr = 0; rr < 4; ++rr) p[rr] = __builtin_amdgcn_exp2f(t[nb][rr] - m_run[nb]);
-        l_run[nb] += (p[0] + p[1]) + (p[2] + p[3]);
-        const uint2 pk = make_uint2(pack_bf16x2(p[0], p[1]), pack_bf16x2(p[2], p[3]));
-        pf[nb] = __builtin_bit_cast(s16x4, pk);
+        uint32_t w[2 * kSubs];
+#pragma unroll
+        for (int sub = 0; sub < kSubs; ++sub) {
+          float p[4];
+#pragma unroll
+          for (int rr = 0; rr < 4; ++rr) p[rr] = __builtin_amdgcn_exp2f(t[sub][nb][rr] - m_run[nb]);
+          l_run[nb] += (p[0] + p[1]) + (p[2] + p[3]);
+          w[2 * sub] = pack_bf16x2(p[0], p[1]);
+          w[2 * sub + 1] = pack_bf16x2(p[2], p[3]);
+        }
+        pf[nb] = __builtin_bit_cast(bf16x8, u32x4{w[0], w[1], w[2], w[3]});
       }
-  #pragma unroll
-      for (int dt = 0; dt < 8; ++dt) {
-        o[0][dt] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(vf[dt], pf[0], o[0][dt], 0, 0, 0);
-        o[1][dt] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(vf[dt], pf[1], o[1][dt], 0, 0, 0);
+      // V^T as the A operand through the transposing read (per page the lane gets rows
+      // 4*bq + n/4 .. of columns 16*dt + 4*(n%4) .. +3): the two pages' halves side by side.
+      // (Read only now: held across the scores and the softmax the V operands would not fit
+      // in the register file beside the two staging sets.)
+      __builtin_amdgcn_sched_barrier(0);
+      {
+        const int vrow = 4 * bq + (n >> 2);
+        const char* vbase = reinterpret_cast<const char*>(lds_v[buf]) + (n & 1) * 8;
+#pragma unroll
+        for (int dt = 0; dt < 8; ++dt) {
+          const char* addr = vbase + swz_v(vrow, 2 * dt + ((n & 3) >> 1)) * 16;
+          const s16x4 v0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(addr));
+          const s16x4 v1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+              (__attribute__((address_space(3))) s16x4*)(addr + kPageGranules * 16));
+          const s16x8 vv = {v0[0], v0[1], v0[2], v0[3], v1[0], v1[1], v1[2], v1[3]};
+          const bf16x8 vf = __builtin_bit_cast(bf16x8, vv);
+          o[0][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, pf[0], o[0][dt], 0, 0, 0);
+          o[1][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, pf[1], o[1][dt], 0, 0, 0);
+        }
       }
     }
     // park step+1; that LDS buffer was last read one step ago
@@ -253,13 +281,18 @@ __global__ __launch_bounds__(PrefillThreads<G>::value) void prefill_attn_kernel(
     __syncthreads();
   };
   int step = 0;
-  for (; step + 1 <= 2 * tile - 2; step += 2) {   // pairs of steps before the diagonal
+  for (; step + 2 <= tile - 1; step += 2) {       // pairs of steps well before the tile's own
     do_step(stage_b, stage_a, step, std::false_type{});
     do_step(stage_a, stage_b, step + 1, std::false_type{});
   }
-  for (; step <= last_step; step += 2) {          // the last two to four steps
+  for (; step <= last_step; ++step) {             // the last one to three steps, one code copy:
     do_step(stage_b, stage_a, step, std::true_type{});
-    if (step + 1 <= last_step) do_step(stage_a, stage_b, step + 1, std::true_type{});
+#pragma unroll
+    for (int j = 0; j < kStage; ++j) {            // the two staging sets trade places
+      const u32x4 x = stage_a[j];
+      stage_a[j] = stage_b[j];
+      stage_b[j] = x;
+    }
   }
 
   // normalise and store: lane (n, bq) owns d = 16*dt + 4*bq + r of query n
