@@ -189,7 +189,7 @@ __global__ __launch_bounds__(PrefillThreads<G>::value) void prefill_attn_kernel(
           for (int kk = 0; kk < 4; ++kk)
             sc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[kk], qf[nb][kk], sc, 0, 0, 0);
 #pragma unroll
-          for (int rr = 0; rr < 4; ++rr) t[sub][nb][rr] = sc[rr] * scale_log2e;
+          for (int rr = 0; rr < 4; ++rr) t[sub][nb][rr] = sc[rr];   // raw: the scale rides on the exponent's fma
         }
       }
       if (kDiag && (step == tile || tail)) {           // the tile's own step, or one at the end
@@ -215,6 +215,7 @@ __global__ __launch_bounds__(PrefillThreads<G>::value) void prefill_attn_kernel(
 #pragma unroll
         for (int sub = 1; sub < kSubs; ++sub)
           loc[nb] = fmaxf(loc[nb], fmaxf(fmaxf(t[sub][nb][0], t[sub][nb][1]), fmaxf(t[sub][nb][2], t[sub][nb][3])));
+        loc[nb] *= scale_log2e;                      // (the scale is positive: max commutes with it)
       }
       const bool grow = loc[0] > m_run[0] + kSlack || loc[1] > m_run[1] + kSlack;
       if (__builtin_amdgcn_ballot_w64(grow) != 0) {
@@ -244,7 +245,8 @@ __global__ __launch_bounds__(PrefillThreads<G>::value) void prefill_attn_kernel(
         for (int sub = 0; sub < kSubs; ++sub) {
           float p[4];
 #pragma unroll
-          for (int rr = 0; rr < 4; ++rr) p[rr] = __builtin_amdgcn_exp2f(t[sub][nb][rr] - m_run[nb]);
+          for (int rr = 0; rr < 4; ++rr)
+            p[rr] = __builtin_amdgcn_exp2f(__builtin_fmaf(t[sub][nb][rr], scale_log2e, -m_run[nb]));
           l_run[nb] += (p[0] + p[1]) + (p[2] + p[3]);
           w[2 * sub] = pack_bf16x2(p[0], p[1]);
           w[2 * sub + 1] = pack_bf16x2(p[2], p[3]);
