@@ -46,6 +46,7 @@ constexpr int kStepGranules = kSubs * kPageGranules;   // 512 granules of K (and
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 constexpr float kSlack = 6.0f;   // scores may exceed the softmax reference by 2^kSlack
+constexpr float kBig = 64.0f;    // = 2^kSlack
 
 __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
   uint32_t r;
@@ -207,22 +208,35 @@ __global__ __launch_bounds__(PrefillThreads<G>::value) void prefill_attn_kernel(
       }
       // The running reference m of a query only has to keep the weights in range, so it is
       // left alone while no score of the step exceeds it by more than kSlack (in log2 units):
-      // the step then needs no exchange between lanes and no rescaling of the state.
-      float loc[2];
+      // the step then needs no maximum, no exchange between lanes and no rescaling of the
+      // state.  The weights are formed against the old reference first; if one of them is
+      // above 2^kSlack (then so is the lane's sum of them - the test - and also while m is
+      // still -inf), the references that have to move are moved and the weights formed again.
+      float w[2][kSubs][4], add[2];
+      auto weights = [&]() __attribute__((always_inline)) {
 #pragma unroll
-      for (int nb = 0; nb < 2; ++nb) {
-        loc[nb] = fmaxf(fmaxf(t[0][nb][0], t[0][nb][1]), fmaxf(t[0][nb][2], t[0][nb][3]));
+        for (int nb = 0; nb < 2; ++nb) {
 #pragma unroll
-        for (int sub = 1; sub < kSubs; ++sub)
-          loc[nb] = fmaxf(loc[nb], fmaxf(fmaxf(t[sub][nb][0], t[sub][nb][1]), fmaxf(t[sub][nb][2], t[sub][nb][3])));
-        loc[nb] *= scale_log2e;                      // (the scale is positive: max commutes with it)
-      }
-      const bool grow = loc[0] > m_run[0] + kSlack || loc[1] > m_run[1] + kSlack;
+          for (int sub = 0; sub < kSubs; ++sub)
+#pragma unroll
+            for (int rr = 0; rr < 4; ++rr)
+              w[nb][sub][rr] = __builtin_amdgcn_exp2f(__builtin_fmaf(t[sub][nb][rr], scale_log2e, -m_run[nb]));
+          add[nb] = ((w[nb][0][0] + w[nb][0][1]) + (w[nb][0][2] + w[nb][0][3])) +
+                    ((w[nb][1][0] + w[nb][1][1]) + (w[nb][1][2] + w[nb][1][3]));
+        }
+      };
+      weights();
+      // (written so that a NaN sum - a masked score against m = -inf - also takes the branch)
+      const bool grow = !(add[0] <= kBig && add[1] <= kBig);
       if (__builtin_amdgcn_ballot_w64(grow) != 0) {
         float alpha[2];
 #pragma unroll
         for (int nb = 0; nb < 2; ++nb) {
-          float mx = loc[nb];
+          float mx = fmaxf(fmaxf(t[0][nb][0], t[0][nb][1]), fmaxf(t[0][nb][2], t[0][nb][3]));
+#pragma unroll
+          for (int sub = 1; sub < kSubs; ++sub)
+            mx = fmaxf(mx, fmaxf(fmaxf(t[sub][nb][0], t[sub][nb][1]), fmaxf(t[sub][nb][2], t[sub][nb][3])));
+          mx *= scale_log2e;                         // (the scale is positive: max commutes with it)
           mx = fmaxf(mx, __shfl_xor(mx, 16, kWave));
           mx = fmaxf(mx, __shfl_xor(mx, 32, kWave));
           // only a query whose own scores outgrew its reference moves it, so a query's
@@ -234,24 +248,17 @@ __global__ __launch_bounds__(PrefillThreads<G>::value) void prefill_attn_kernel(
         }
 #pragma unroll
         for (int i = 0; i < 16; ++i) o[i >> 3][i & 7] *= alpha[i >> 3];
+        weights();
       }
       // weights of the step's 32 tokens as the B operand of the 32-deep value product:
       // the first page's four in k-slots 0..3, the second page's in 4..7
       bf16x8 pf[2];
 #pragma unroll
       for (int nb = 0; nb < 2; ++nb) {
-        uint32_t w[2 * kSubs];
-#pragma unroll
-        for (int sub = 0; sub < kSubs; ++sub) {
-          float p[4];
-#pragma unroll
-          for (int rr = 0; rr < 4; ++rr)
-            p[rr] = __builtin_amdgcn_exp2f(__builtin_fmaf(t[sub][nb][rr], scale_log2e, -m_run[nb]));
-          l_run[nb] += (p[0] + p[1]) + (p[2] + p[3]);
-          w[2 * sub] = pack_bf16x2(p[0], p[1]);
-          w[2 * sub + 1] = pack_bf16x2(p[2], p[3]);
-        }
-        pf[nb] = __builtin_bit_cast(bf16x8, u32x4{w[0], w[1], w[2], w[3]});
+        l_run[nb] += add[nb];
+        pf[nb] = __builtin_bit_cast(
+            bf16x8, u32x4{pack_bf16x2(w[nb][0][0], w[nb][0][1]), pack_bf16x2(w[nb][0][2], w[nb][0][3]),
+                          pack_bf16x2(w[nb][1][0], w[nb][1][1]), pack_bf16x2(w[nb][1][2], w[nb][1][3])});
       }
       // V^T as the A operand through the transposing read (per page the lane gets rows
       // 4*bq + n/4 .. of columns 16*dt + 4*(n%4) .. +3): the two pages' halves side by side.
