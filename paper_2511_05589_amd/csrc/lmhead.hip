@@ -650,40 +650,48 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   const int total = my_tiles * nkd;            // slabs this workgroup consumes
   const int ld_row = 32 * wave + (lane >> 3);
   const uint32_t ld_g = ((lane & 7) ^ (lane >> 4)) * 16;
-  int w_n = 0, w_tile = lane_id, w_kd = 0, w_slot = 0;
-  int h_n = 0, h_kd = 0, h_slot = 0;
+  int w_tile = lane_id, w_kd = 0, w_slot = 0;
+  int h_kd = 0, h_slot = 0;
   const char* wbase = reinterpret_cast<const char*>(weight);
   const char* hbase = reinterpret_cast<const char*>(hidden);
-  auto issue_w = [&]() __attribute__((always_inline)) {
-    char* dst = smem + w_slot * kGmSlab + (4 * wave) * 1024;
+  // one of the four loads of this wave's eighth of the W / hidden slab at the cursor
+  auto w_load = [&](int j) __attribute__((always_inline)) {
+    char* dst = smem + w_slot * kGmSlab + (4 * wave + j) * 1024;
     const uint32_t koff = static_cast<uint32_t>(w_kd) * (kMfBK * 2) + ld_g;
-    const int vrow = w_tile * kGmBM + ld_row;
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const int v = min(vrow + 8 * j, V - 1);      // rows past V re-read the last row (masked later)
-      __builtin_amdgcn_global_load_lds(wbase + (static_cast<uint32_t>(v) * pitch + (koff ^ ((j & 1) * 64))),
-                                       dst + j * 1024, 16, 0, 0);
-    }
+    const int v = min(w_tile * kGmBM + ld_row + 8 * j, V - 1);   // rows past V re-read the last row (masked later)
+    __builtin_amdgcn_global_load_lds(wbase + (static_cast<uint32_t>(v) * pitch + (koff ^ ((j & 1) * 64))), dst,
+                                     16, 0, 0);
+  };
+  auto w_advance = [&]() __attribute__((always_inline)) {
     w_slot = w_slot + 1 == kWSlots ? 0 : w_slot + 1;
-    ++w_n;
     if (++w_kd == nkd) {
       w_kd = 0;
       w_tile += n_lanes;
     }
   };
-  auto issue_h = [&]() __attribute__((always_inline)) {
-    char* dst = smem + kHBase + h_slot * kGmSlab + (4 * wave) * 1024;
+  auto h_load = [&](int j) __attribute__((always_inline)) {
+    char* dst = smem + kHBase + h_slot * kGmSlab + (4 * wave + j) * 1024;
     const uint32_t koff = static_cast<uint32_t>(h_kd) * (kMfBK * 2) + ld_g;
-    const int crow = c0 + ld_row;
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const int c = min(crow + 8 * j, C - 1);      // rows past C duplicate the last row (unused)
-      __builtin_amdgcn_global_load_lds(hbase + (static_cast<uint32_t>(c) * pitch + (koff ^ ((j & 1) * 64))),
-                                       dst + j * 1024, 16, 0, 0);
-    }
+    const int c = min(c0 + ld_row + 8 * j, C - 1);               // rows past C duplicate the last row (unused)
+    __builtin_amdgcn_global_load_lds(hbase + (static_cast<uint32_t>(c) * pitch + (koff ^ ((j & 1) * 64))), dst,
+                                     16, 0, 0);
+  };
+  auto h_advance = [&]() __attribute__((always_inline)) {
     h_slot = h_slot + 1 == kHSlots ? 0 : h_slot + 1;
-    ++h_n;
     if (++h_kd == nkd) h_kd = 0;
+  };
+  // Load k (0..7) of the set a barrier opens: the shallow stream's slab first, then the deep
+  // one's.  Past the workgroup's last slab the loads re-read clamped rows into ring slots
+  // nobody reads any more, so none of them needs a condition.
+  auto load_one = [&](int k) __attribute__((always_inline)) {
+    const bool is_h = W_DEEP ? k < 4 : k >= 4;
+    if (is_h) {
+      h_load(k & 3);
+      if ((k & 3) == 3) h_advance();
+    } else {
+      w_load(k & 3);
+      if ((k & 3) == 3) w_advance();
+    }
   };
 
   // this lane owns batch rows c0 + 64*wq + 32*nt + l32; their given tokens are fetched
@@ -697,19 +705,18 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     tgt[nt] = c < C ? target[c] : -1;
   }
 
-  // prologue: slab 0 lands, then the steady order "hidden(d+2), W(d+3)" is set up
-  auto issue_shallow = [&]() __attribute__((always_inline)) {
-    if (W_DEEP) { if (h_n < total) issue_h(); } else { if (w_n < total) issue_w(); }
-  };
-  auto issue_deep = [&]() __attribute__((always_inline)) {
-    if (W_DEEP) { if (w_n < total) issue_w(); } else { if (h_n < total) issue_h(); }
-  };
-  issue_shallow();
-  issue_deep();
-  issue_deep();
+  // prologue: slab 0 of both streams and slab 1 of the deep one land; then the steady order
+  // begins - after the barrier that ends slab d, the shallow stream's slab d+2 and the deep
+  // one's slab d+3 go out, one load at a time between the matrix products of the next 32
+  // (issued in a bunch they keep all eight waves at the issue stage while the address unit
+  // works through them, and the matrix pipes idle).  The first two loads of the set that the
+  // prologue's barrier opens go out here, the other six with the products of slab 0.
+  for (int k = 0; k < 4; ++k) load_one(k);          // shallow slab 0
+  for (int k = 4; k < 8; ++k) load_one(k);          // deep slab 0
+  for (int k = 4; k < 8; ++k) load_one(k);          // deep slab 1
   asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
-  issue_shallow();
-  issue_deep();
+  load_one(0);
+  load_one(1);
 
   u32x4 a[2][4], b[2][2];
   int wslot = 0, hslot = 0;                     // ring slots of the slab being consumed
@@ -737,8 +744,10 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     for (int i = 0; i < 8; ++i)
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i >> 1][i & 1][r] = 0.0f;
-    auto products = [&](auto bufc) __attribute__((always_inline)) {
-      constexpr int buf = decltype(bufc)::value;
+    // eight products from operand buffer `buf`; if `issue`, loads FIRST and FIRST+1 of the
+    // open set go out after the second and the sixth of them
+    auto products = [&](auto bufc, auto firstc, const bool issue) __attribute__((always_inline)) {
+      constexpr int buf = decltype(bufc)::value, kFirst = decltype(firstc)::value;
       const bf16x8 fb0 = __builtin_bit_cast(bf16x8, b[buf][0]);
       const bf16x8 fb1 = __builtin_bit_cast(bf16x8, b[buf][1]);
 #pragma unroll
@@ -746,42 +755,47 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
         const bf16x8 fa = __builtin_bit_cast(bf16x8, a[buf][rb]);
         acc[rb][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa, fb0, acc[rb][0], 0, 0, 0);
         acc[rb][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa, fb1, acc[rb][1], 0, 0, 0);
+        if (rb == 0 || rb == 2) {
+          __builtin_amdgcn_sched_barrier(0);
+          if (issue) load_one(kFirst + (rb >> 1));
+          __builtin_amdgcn_sched_barrier(0);
+        }
       }
     };
+    using L0 = std::integral_constant<int, 0>;
+    using L2 = std::integral_constant<int, 2>;
+    using L4 = std::integral_constant<int, 4>;
+    using L6 = std::integral_constant<int, 6>;
 
     for (int kd = 0; kd < nkd; ++kd, ++d) {
       read_operands(I1{}, I1{});
       lds_wait6<6>(a[0], b[0]);
-      products(I0{});
+      products(I0{}, L2{}, true);
       read_operands(I0{}, I2{});
       lds_wait6<6>(a[1], b[1]);
-      products(I1{});
+      products(I1{}, L4{}, true);
       read_operands(I1{}, I3{});
       lds_wait6<6>(a[0], b[0]);
-      products(I0{});
+      products(I0{}, L6{}, true);
       // every LDS read of slab d is complete; the other operand buffer is tied as well so
       // that the products just issued from it stay above this wait
       asm volatile("s_waitcnt lgkmcnt(0)"
                    : "+v"(a[1][0]), "+v"(a[1][1]), "+v"(a[1][2]), "+v"(a[1][3]), "+v"(b[1][0]),
                      "+v"(b[1][1]), "+v"(a[0][0]), "+v"(a[0][1]), "+v"(a[0][2]), "+v"(a[0][3]),
                      "+v"(b[0][0]), "+v"(b[0][1])::"memory");
-      if (d + 1 < total) {
-        // slab d+1 has landed (this wave's part: only the deep stream's slab d+2 is younger) ...
-        if (d + 2 < total) {
-          asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
-        } else {
-          asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        }
+      const bool more = d + 1 < total;
+      if (more) {
+        // slab d+1 has landed (this wave's part: only the deep stream's slab d+2, the newest
+        // four loads, is younger) ...
+        asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
         asm volatile("s_barrier" ::: "memory");   // ... for every wave, and all are done reading slab d
-        issue_shallow();                          // slab d+2 of the shallow stream, into the slot of slab d
-        issue_deep();                             // slab d+3 of the deep stream, likewise
         wslot = wslot + 1 == kWSlots ? 0 : wslot + 1;
         hslot = hslot + 1 == kHSlots ? 0 : hslot + 1;
         wb = lds0 + wslot * kGmSlab;
         hb = lds0 + kHBase + hslot * kGmSlab;
         read_operands(I0{}, I0{});                // first operands of slab d+1, under the products below
       }
-      products(I1{});
+      products(I1{}, L0{}, more);                 // with the first two loads into the slots of slab d
     }
 
     const bool tail = v0 + kGmBM > V;   // only the last tile can hold rows past V
