@@ -307,8 +307,9 @@ __device__ __forceinline__ void lm_given_block(const f32x16& acc, LmLaneState& s
 // Every wave issues a quarter of each slab and unit, one load at a time between the matrix
 // products.  The outstanding-load counter of a wave retires in order, so the issue order is
 // chosen such that what a wait needs is always older than what may stay in flight: per slab
-// d hidden(2d+2), W(d+1) - the last two of its four loads after the middle barrier - then
-// hidden(2d+3).  The compiler cannot count LDS-direct loads per buffer (it
+// d W(d+1) first (it comes from HBM and needs the longest lead), then hidden(2d+2) - the
+// last two of its four loads after the middle barrier - then hidden(2d+3).  The compiler
+// cannot count LDS-direct loads per buffer (it
 // would drain them all before any LDS read), so the operand reads are inline ds_read_b128
 // and every wait is explicit.  80 KB of LDS per workgroup: two workgroups fill a CU's 160 KB.
 constexpr int kNW = 2;                              // W ring slabs
@@ -425,7 +426,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   }
 
   // prologue.  A wave's loads complete in issue order, and that order is, per slab d:
-  // hidden(2d+2) and half of W(d+1) before the middle barrier, the rest of W(d+1) and
+  // W(d+1) and half of hidden(2d+2) before the middle barrier, the rest of hidden(2d+2) and
   // hidden(2d+3) after it.  So at the top the wave may leave its newest four loads
   // (hidden(2d+1)) in flight and knows W(d) and hidden(2d) have landed; at mid-slab it may
   // leave the six issued since the top and knows hidden(2d+1) has.
@@ -499,7 +500,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
             // products (three per group of eight).  Issued in a bunch they keep every wave
             // of the CU at the issue stage while the address unit works through them, and the
             // matrix pipes idle meanwhile; spread out they cost the products nothing.
-            // Order: hidden (d+1, half 0), W slab d+1 (its slot and that unit's are free since
+            // Order: W slab d+1, hidden (d+1, half 0) (its slot and that slab's are free since
             // the top barrier), then hidden (d+1, half 1) after the middle barrier has freed
             // the slot of (d, half 0).  Past the last slab the loads re-read clamped rows into
             // ring slots nobody reads any more.
@@ -507,11 +508,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
               const int q = 3 * (2 * half + grp) + (m == 1 ? 0 : m == 4 ? 1 : 2);   // 0 .. 11
               __builtin_amdgcn_sched_barrier(0);
               if (q < 4) {
-                h_load(q);
-                if (q == 3) h_advance();
+                w_load(q);
+                if (q == 3) w_advance();
               } else if (q < 8) {
-                w_load(q - 4);
-                if (q == 7) w_advance();
+                h_load(q - 4);
+                if (q == 7) h_advance();
               } else {
                 h_load(q - 8);
                 if (q == 11) h_advance();
