@@ -411,3 +411,57 @@ def make_is_inputs(cfg: ISConfig, *, rng: Optional[np.random.Generator] = None,
             "cu_seqlens": cu.astype(np.int32), "split": split, "mask": mask,
             "logp_cur": logp_cur, "logp_buf": logp_buf, "logp_roll": logp_roll,
             "adv": adv, "eps_low": cfg.eps_low, "eps_high": cfg.eps_high}
+
+
+# --------------------------------------------------------------------------
+# Stand-in for the transformer under the rollout loop: per-position tensors are seeded noise
+# --------------------------------------------------------------------------
+class StandInPolicy:
+    """Seeded stand-in for a decoder under successive policy versions (no arithmetic of the
+    method here: the rollout loop and the tests both draw their inputs from it).
+
+    Trajectory tr = input * samples + sample has positions 0 .. prompt_len + resp_len - 1.
+    Under policy version `ver`, position p of trajectory tr has a query [Hq, D], a key and a
+    value [Hkv, D] and a final hidden state [H]: normal noise keyed by (seed, tr, ver), in
+    the storage dtype.  The LM-head matrix of version ver is W0 + drift * ver * W1 (rounded to
+    the storage dtype), so that successive policies differ a little, as after a training step.
+    """
+
+    def __init__(self, seed: int, prompt_len, resp_len, Hq: int, Hkv: int, D: int, H: int, V: int,
+                 dtype: str = BF16, drift: float = 0.05):
+        self.seed = int(seed)
+        self.prompt_len = np.asarray(prompt_len, dtype=np.int64)
+        self.resp_len = np.asarray(resp_len, dtype=np.int64)
+        self.samples = int(self.resp_len.shape[1])
+        self.Hq, self.Hkv, self.D, self.H, self.V = Hq, Hkv, D, H, V
+        self.dtype = dtype
+        self.drift = float(drift)
+        self.scale = 1.0 / float(np.sqrt(D))
+        self._tables = {}
+        self._weights = {}
+        rng = np.random.default_rng([self.seed, 0x57])
+        self._w0 = rng.normal(0.0, 0.05, size=(V, H)).astype(np.float32)
+        self._w1 = rng.normal(0.0, 0.05, size=(V, H)).astype(np.float32)
+
+    def length(self, tr: int) -> int:
+        i, s = divmod(int(tr), self.samples)
+        return int(self.prompt_len[i] + self.resp_len[i, s])
+
+    def tables(self, tr: int, ver: int) -> dict:
+        key = (int(tr), int(ver))
+        if key not in self._tables:
+            rng = np.random.default_rng([self.seed, 1 + int(tr), int(ver)])
+            L = self.length(tr)
+            self._tables[key] = {
+                "q": _normal_storage(rng, (L, self.Hq, self.D), self.dtype),
+                "k": _normal_storage(rng, (L, self.Hkv, self.D), self.dtype),
+                "v": _normal_storage(rng, (L, self.Hkv, self.D), self.dtype),
+                "hidden": _normal_storage(rng, (L, self.H), self.dtype),
+            }
+        return self._tables[key]
+
+    def weight(self, ver: int) -> np.ndarray:
+        ver = int(ver)
+        if ver not in self._weights:
+            self._weights[ver] = to_storage(self._w0 + self.drift * ver * self._w1, self.dtype)
+        return self._weights[ver]
