@@ -50,7 +50,9 @@ def parse_args():
 
 
 def algorithmic_bytes(cfg, inp, isb):
-    """Bytes the method itself must move, per launch (the figures the design doc states)."""
+    """Bytes the method itself must move, per launch: K and V rows of every context token, the
+    block-table entries used, q in and out; W once plus hidden and the per-row outputs; 17 bytes
+    per token of the ratio batch."""
     import numpy as np
     eb = cfg.elem_bytes
     ctx = inp["ctx_len"].astype(np.int64)
