@@ -187,6 +187,80 @@ def kv_page_fill(k, v, cu_seqlens, block_table, k_cache, v_cache):
             v_cache[page, :, t % P, :] = v[s0 + t]
 
 
+def pool_commands_apply(cmds, n_slot_cmds, n_page_cmds, seq_id, ctx_len, step, block_table):
+    """The rollout manager's per-step commands applied to the pool state (in place):
+    n_slot_cmds x (slot, trajectory or -1, ctx_len, step), then n_page_cmds x (slot, page index,
+    physical page)."""
+    cmds = [int(x) for x in cmds]
+    for i in range(n_slot_cmds):
+        slot, tr, n, g = cmds[4 * i:4 * i + 4]
+        seq_id[slot], ctx_len[slot], step[slot] = tr, n, g
+    base = 4 * n_slot_cmds
+    for i in range(n_page_cmds):
+        slot, idx, page = cmds[base + 3 * i:base + 3 * i + 3]
+        block_table[slot, idx] = page
+
+
+def kv_append(k_new, v_new, block_table, ctx_len, k_cache, v_cache):
+    """One decode step's cache update (in place): row c of k_new / v_new [C, Hkv, D] is the key /
+    value of the position being decoded by request c, token index ctx_len[c] - 1 of its context,
+    i.e. page block_table[c, t // P], slot t % P.  Requests with ctx_len <= 0 hold nothing."""
+    P = k_cache.shape[2]
+    for c in range(len(ctx_len)):
+        t = int(ctx_len[c]) - 1
+        if t < 0:
+            continue
+        page = int(block_table[c, t // P])
+        k_cache[page, :, t % P, :] = k_new[c]
+        v_cache[page, :, t % P, :] = v_new[c]
+
+
+# --------------------------------------------------------------------------
+# The buffer of Section 4 ("Buffering of Partial Trajectories").  Per trajectory i the
+# buffer holds the generated tokens and L_i, the log-prob of every token under the policy
+# of the stage that generated it; Eq. 6: L_i is the concatenation, along the token axis,
+# of the pieces L_i^(1), ..., L_i^(K) of the K stages the trajectory was generated over.
+# Here the buffer is a dict trajectory -> list of pieces, one piece per stage that
+# generated tokens of it: (stage, [tokens], [log-probs]).
+# --------------------------------------------------------------------------
+def buffer_append(buffer, traj, stage, token, logprob):
+    """The token a request just sampled joins the piece of the current stage (a new piece is
+    opened when the trajectory has none for this stage yet)."""
+    pieces = buffer.setdefault(int(traj), [])
+    if not pieces or pieces[-1][0] != int(stage):
+        pieces.append((int(stage), [], []))
+    pieces[-1][1].append(int(token))
+    pieces[-1][2].append(float(logprob))
+
+
+def buffer_concat(buffer, trajs, stage):
+    """Eq. 6 for the trajectories of a training batch formed in `stage`.  For each, the pieces
+    are concatenated in stage order.  Returns the packed batch the ratio of Eq. 8 is formed on:
+      cu_seqlens [B+1], tokens [N]
+      logp_buf  [N]  L_i restricted to the pieces of EARLIER stages (NaN on this stage's piece)
+      logp_roll [N]  this stage's piece (NaN on the earlier ones)
+      split [B]      tokens of trajectory b that come from earlier stages
+    The earlier pieces form a prefix because stages follow each other in time."""
+    cu, toks, lbuf, lroll, split = [0], [], [], [], []
+    for tr in trajs:
+        pieces = sorted(buffer.get(int(tr), []), key=lambda pc: pc[0])
+        n_old = 0
+        for st, tk, lp in pieces:
+            toks.extend(tk)
+            if st < stage:
+                lbuf.extend(lp)
+                lroll.extend([np.nan] * len(lp))
+                n_old += len(lp)
+            else:
+                lbuf.extend([np.nan] * len(lp))
+                lroll.extend(lp)
+        split.append(n_old)
+        cu.append(len(toks))
+    return {"cu_seqlens": np.asarray(cu, dtype=np.int64), "tokens": np.asarray(toks, dtype=np.int64),
+            "logp_buf": np.asarray(lbuf, dtype=np.float64), "logp_roll": np.asarray(lroll, dtype=np.float64),
+            "split": np.asarray(split, dtype=np.int64)}
+
+
 # --------------------------------------------------------------------------
 # O2: LM head + log-softmax + Gumbel-max sample + chosen-token log-prob
 # --------------------------------------------------------------------------
