@@ -342,6 +342,137 @@ int copris_rollout_schedule(const int32_t* prompt_len, const int32_t* resp_len,
                             int page_size, int max_stages, copris_stage_stats* stats,
                             int32_t* batch_out, int* n_stages);
 
+/* ------------------------------------------------------------------------
+ * Rollout manager, one decode step at a time: the same rules as
+ * copris_rollout_schedule for a caller that runs the kernels between the calls.
+ * HOST functions; every pointer is host memory.
+ *
+ * The manager takes every decision of Section 4.  "Concurrency-Controlled
+ * Generation": which trajectory occupies which of the `pool` (N') slots; an emptied
+ * slot is refilled before the next step.  "Prioritized Resumption": paused
+ * trajectories enter first, in (input, sample) order, and are re-prefilled with
+ * prompt + generated tokens.  "Early Termination": next_step answers
+ * COPRIS_ROLLOUT_STAGE_END as soon as `batch_inputs` (B) inputs have all their
+ * samples.  "Buffering of Partial Trajectories": end_stage pauses what still runs
+ * and names the batch, with each trajectory's number of tokens from earlier stages
+ * (the boundary between the buffered pieces of Eq. 6 and this stage's piece: `split`
+ * of copris_is_ratio).  It also owns the KV page allocator: pages are taken from a
+ * free list in `page_order` (NULL: ascending), held by running requests only, and
+ * returned when a request finishes or is paused (the next policy invalidates them).
+ *
+ * A trajectory ends after resp_len[input][sample] tokens, or earlier when the caller
+ * reports an end-of-sequence token with copris_rollout_stop.  With lengths known in
+ * advance a whole stage can be enqueued without reading anything back from the device.
+ *
+ * Protocol:  create;  per stage:  begin_stage;  loop { next_step -> STEP: run the
+ * plan, optionally copris_rollout_stop;  STAGE_END: leave the loop;  EXHAUSTED: no
+ * batch can be completed any more };  end_stage;  ...  destroy.
+ *
+ * copris_rollout_create   num_pages >= pool * ceil(max(prompt + resp) / page_size), so
+ *                         that no request is ever preempted; page_order [num_pages] a
+ *                         permutation of 0..num_pages-1 or NULL; *out receives the
+ *                         handle (owned by the caller until copris_rollout_destroy).
+ * copris_rollout_begin_stage  returns the stage index (>= 0) or a negative error.
+ * copris_rollout_next_step    fills *plan; the arrays it points to belong to the
+ *                         manager and stay valid until the next call on the handle.
+ *                         Returns COPRIS_ROLLOUT_STEP / _STAGE_END / _EXHAUSTED or a
+ *                         negative error.  A returned STEP counts as run.
+ * copris_rollout_stop     slots [n]: requests whose last generated token ended them.
+ * copris_rollout_end_stage    only after STAGE_END.  stats [1]; batch_inputs_out
+ *                         [batch_inputs]; batch_traj_out [batch_inputs * samples][3] =
+ *                         {trajectory (input * samples + sample), response tokens,
+ *                         tokens generated in earlier stages}.
+ * Not thread-safe per handle.  Errors: COPRIS_EINVAL.
+ * ------------------------------------------------------------------------ */
+#define COPRIS_ROLLOUT_STEP      0
+#define COPRIS_ROLLOUT_STAGE_END 1
+#define COPRIS_ROLLOUT_EXHAUSTED 2
+
+typedef struct copris_rollout copris_rollout;
+
+typedef struct copris_rollout_plan {
+  int32_t stage;          /* stage (policy version) the step belongs to */
+  int32_t n_active;       /* requests that run in this step */
+  int32_t n_entered;      /* requests that enter the pool before this step */
+  int32_t n_finishing;    /* requests that generate their last token in this step */
+  int32_t n_slot_cmds;    /* slot commands in cmds */
+  int32_t n_page_cmds;    /* page commands in cmds */
+  const int32_t* slot_traj;    /* [pool] trajectory in every slot during the step, -1 = idle */
+  const int32_t* entered;      /* [n_entered][4] slot, trajectory, tokens to (re-)prefill
+                                  (prompt + generated), 1 if resumed from the buffer */
+  const int32_t* finishing;    /* [n_finishing] slots */
+  const int32_t* cmds;         /* the input of copris_rollout_apply: n_slot_cmds x {slot,
+                                  trajectory or -1, ctx_len, step}, then n_page_cmds x {slot,
+                                  page index, physical page} */
+  const int32_t* block_table;  /* [pool][max_pages] the manager's copy of the block table */
+} copris_rollout_plan;
+
+int copris_rollout_create(const int32_t* prompt_len, const int32_t* resp_len, int n_inputs,
+                          int samples, int pool, int batch_inputs, int page_size, int64_t num_pages,
+                          const int32_t* page_order, copris_rollout** out);
+void copris_rollout_destroy(copris_rollout* h);
+int copris_rollout_max_pages(const copris_rollout* h);       /* block-table row length */
+int64_t copris_rollout_free_pages(const copris_rollout* h);  /* pages on the free list now */
+int copris_rollout_begin_stage(copris_rollout* h);
+int copris_rollout_next_step(copris_rollout* h, copris_rollout_plan* plan);
+int copris_rollout_stop(copris_rollout* h, const int32_t* slots, int n);
+int copris_rollout_end_stage(copris_rollout* h, copris_stage_stats* stats, int32_t* batch_inputs_out,
+                             int32_t* batch_traj_out);
+
+/* ------------------------------------------------------------------------
+ * Device side of the rollout loop: the per-slot state of the pool and the buffer of
+ * Section 4 ("Buffering of Partial Trajectories") live in device memory, so that a
+ * stage runs without a read-back per token.  DEVICE pointers, enqueued on `stream`.
+ *
+ * Pool state, one entry per slot:  seq_id [pool] int64 (trajectory, -1 = idle; also the
+ * Philox stream id of copris_lmhead_logprob), ctx_len [pool] int32 (cached tokens incl.
+ * the position being decoded; 0 = idle), step [pool] int32 (index of the token being
+ * generated), block_table [pool][max_pages] int32.
+ * Buffer, one row per trajectory:  buf_token, buf_tag int32 and buf_logp fp32
+ * [n_traj][max_resp]: the sampled token, the stage that generated it and its log-prob
+ * under that stage's policy.  By Eq. 6 a trajectory's buffered log-probs are its
+ * per-stage pieces concatenated in token order, which is how a row fills up.
+ *
+ * copris_rollout_apply   applies one plan's commands (copris_rollout_plan.cmds, copied
+ *     to the device by the caller): sets seq_id / ctx_len / step of the slots whose
+ *     occupant changed and the block-table entries of newly taken pages.
+ * copris_kv_append       k_new, v_new [C, Hkv, D] dtype: the new position's key / value
+ *     of every slot goes to token position ctx_len[c] - 1 of its pages
+ *     (k_cache[block_table[c][t / P]][kvh][t % P][:]); slots with ctx_len <= 0 are
+ *     skipped.  Supported: D % 8 == 0 (bf16) or D % 4 == 0 (fp32).
+ * copris_traj_append     after sampling: for every slot with seq_id >= 0 stores
+ *     token[c], logprob[c] and `stage` at buf_*[seq_id[c]][step[c]] and advances the
+ *     slot (step[c] += 1, ctx_len[c] += 1).  step[c] >= max_resp stores nothing.
+ * copris_traj_gather     packs a training batch out of the buffer (Eq. 6): for
+ *     trajectory traj[b], tokens j = cu_seqlens[b] + t, t < cu_seqlens[b+1] - cu_seqlens[b]:
+ *       tokens_out[j] = buf_token[traj[b]][t]
+ *       earlier = buf_tag[traj[b]][t] < stage
+ *       logp_buf_out[j]  = earlier ? buf_logp[..][t] : NaN      (the buffered pieces)
+ *       logp_roll_out[j] = earlier ? NaN : buf_logp[..][t]      (this stage's piece)
+ *       split_out[b] = number of tokens with earlier == true
+ *     which are the inputs of copris_lmhead_token_logprob, copris_is_ratio and
+ *     copris_grpo_surrogate.
+ * All four: COPRIS_EINVAL on null pointers / bad sizes, COPRIS_ELAUNCH on a launch
+ * error; n == 0 / C == 0 / B == 0 enqueue nothing.
+ * ------------------------------------------------------------------------ */
+int copris_rollout_apply(const int32_t* cmds, int n_slot_cmds, int n_page_cmds, int64_t* seq_id,
+                         int32_t* ctx_len, int32_t* step, int32_t* block_table, int pool,
+                         int max_pages, void* stream);
+
+int copris_kv_append(const void* k_new, const void* v_new, const int32_t* block_table,
+                     const int32_t* ctx_len, void* k_cache, void* v_cache, int C, int Hkv, int D,
+                     int page_size, int max_pages, int64_t num_pages, int dtype, void* stream);
+
+int copris_traj_append(const int32_t* token, const float* logprob, const int64_t* seq_id,
+                       int32_t* step, int32_t* ctx_len, int stage, int32_t* buf_token,
+                       float* buf_logp, int32_t* buf_tag, int C, int64_t n_traj, int max_resp,
+                       void* stream);
+
+int copris_traj_gather(const int32_t* buf_token, const float* buf_logp, const int32_t* buf_tag,
+                       const int32_t* traj, const int32_t* cu_seqlens, int stage,
+                       int32_t* tokens_out, float* logp_buf_out, float* logp_roll_out,
+                       int32_t* split_out, int B, int64_t n_traj, int max_resp, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -5,11 +5,16 @@ import os
 import shutil
 import subprocess
 import sys
+from concurrent.futures import ThreadPoolExecutor
 
 PKG_DIR = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(PKG_DIR, "csrc")
 LIB_PATH = os.path.join(PKG_DIR, "libcopris.so")
-SOURCES = ["copris_api.hip", "decode_attn.hip", "prefill_attn.hip", "lmhead.hip", "is_ratio.hip", "rollout_manager.cpp"]
+OBJ_DIR = os.path.join(PKG_DIR, "_build")
+SOURCES = ["copris_api.hip", "decode_attn.hip", "prefill_attn.hip", "lmhead.hip", "is_ratio.hip",
+           "rollout_manager.cpp", "rollout_device.hip"]
+# the host pass warns that it does not know the packed-fp32 feature: harmless
+NOISE = ("is not a recognized feature", "1 warning generated", "warnings generated")
 
 
 def hipcc_path() -> str:
@@ -19,25 +24,41 @@ def hipcc_path() -> str:
     raise RuntimeError("hipcc not found")
 
 
-def build(verbose: bool = False) -> str:
-    """Compile every HIP source for gfx950 and link the shared library."""
-    cmd = [hipcc_path(), "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
-           # packed-FP32 arithmetic is switched off for all device code
-           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-           "-Wno-unused-command-line-argument",
-           "-I", os.path.join(os.path.dirname(PKG_DIR), "include"),
-           "-o", LIB_PATH] + [os.path.join(CSRC, s) for s in SOURCES]
+def compile_flags() -> list:
+    return ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
+            # packed-FP32 arithmetic is switched off for all device code
+            "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+            "-Wno-unused-command-line-argument",
+            "-I", os.path.join(os.path.dirname(PKG_DIR), "include")]
+
+
+def _run(cmd, verbose):
     if verbose:
         print(" ".join(cmd), flush=True)
     res = subprocess.run(cmd, capture_output=True, text=True)
-    # the host pass warns that it does not know the packed-fp32 feature: harmless
-    noise = ("is not a recognized feature", "1 warning generated", "warnings generated")
-    err = "\n".join(l for l in res.stderr.splitlines() if not any(n in l for n in noise))
     if res.returncode != 0:
         raise RuntimeError("hipcc failed:\n" + res.stderr)
+    err = "\n".join(l for l in res.stderr.splitlines() if not any(n in l for n in NOISE))
     if verbose and err.strip():
         print(err, file=sys.stderr)
-    return LIB_PATH
+
+
+def build(verbose: bool = False, lib_path: str = LIB_PATH, extra_flags=()) -> str:
+    """Compile every HIP source for gfx950 (one hipcc process per file, side by side) and
+    link the shared library."""
+    hipcc = hipcc_path()
+    os.makedirs(OBJ_DIR, exist_ok=True)
+    tag = os.path.splitext(os.path.basename(lib_path))[0]
+    objs = [os.path.join(OBJ_DIR, f"{tag}.{s}.o") for s in SOURCES]
+    flags = compile_flags() + list(extra_flags)
+    with ThreadPoolExecutor(max_workers=min(len(SOURCES), os.cpu_count() or 1)) as pool:
+        jobs = [pool.submit(_run, [hipcc] + flags + ["-c", os.path.join(CSRC, s), "-o", o], verbose)
+                for s, o in zip(SOURCES, objs)]
+        for j in jobs:
+            j.result()
+    _run([hipcc, "--offload-arch=gfx950", "-fPIC", "-shared", "-o", lib_path] + list(extra_flags) + objs,
+         verbose)
+    return lib_path
 
 
 if __name__ == "__main__":

@@ -1,31 +1,29 @@
-"""A fixed-concurrency rollout loop that drives the library's kernels end to end
-(Section 4: Concurrency-Controlled Generation, Early Termination, Buffering of Partial
-Trajectories with Eq. 6, Prioritized Resumption; Eq. 8 and Eq. 2-4 on the training batch).
+"""Rollout stages under the library's rollout manager, with the pool state and the buffer of
+partial trajectories resident on the device (Section 4: Concurrency-Controlled Generation,
+Early Termination, Buffering of Partial Trajectories with Eq. 6, Prioritized Resumption;
+Eq. 8 and Eq. 2-4 on the training batch).
 
-The transformer is replaced by a stand-in (`workloads.StandInPolicy`): the query, key, value
-and final hidden state of a trajectory position are seeded noise per policy version, and a
-trajectory stops at a given length.  Everything around it is the real path:
+Who does what:
 
-  * a pool of `pool` requests, refilled whenever one finishes, paused trajectories first;
-  * a KV page allocator (free list); pages are released when a request finishes or is
-    paused, because a new policy version invalidates them;
-  * (re-)prefill of every request that enters the pool: `copris_prefill_attn` rebuilds the
-    pages of prompt + generated tokens under the current version;
-  * one decode step per iteration: the new position's key / value are appended to its page
-    (a copy, the one step a decoder layer would do that this library does not), then
-    `copris_decode_attn` over the active set and `copris_lmhead_logprob` sample a token and
-    its log-prob, which goes to the trajectory's buffer tagged with the stage;
-  * a stage stops as soon as `batch_inputs` inputs have all their samples; on that batch
-    `copris_lmhead_token_logprob` gives the current policy's log-probs of the buffered tokens,
-    `copris_is_ratio` the cross-stage ratios and `copris_grpo_surrogate` the clipped surrogate.
+  * `copris_rollout_*` (host C++) takes every scheduling decision: the trajectory in every
+    pool slot, what enters and is (re-)prefilled, the KV pages of every request, when the
+    stage stops, which inputs leave as the batch and how many of each trajectory's tokens
+    come from earlier stages.  This module asks it before every step and decides nothing.
+  * The device keeps, between steps, the per-slot state (`seq_id`, `ctx_len`, `step`, block
+    table) and the buffer rows of every trajectory (token, log-prob, stage tag).  Per step it
+    runs `copris_rollout_apply` (the manager's commands), `copris_prefill_attn` for entering
+    requests, `copris_kv_append`, `copris_decode_attn`, `copris_lmhead_logprob` and
+    `copris_traj_append`; per batch `copris_traj_gather`, `copris_lmhead_token_logprob`,
+    `copris_is_ratio` and `copris_grpo_surrogate`.  Nothing is read back inside a stage; the
+    host waits for the device once per stage, when it collects the batch's results.
+  * The transformer is a stand-in (`workloads.StandInPolicy`): query, key, value and final
+    hidden state of a trajectory position are seeded noise per policy version, held in
+    device tables here and looked up by row; a trajectory ends at a given length, which is
+    what lets the manager plan a stage without waiting for tokens.
 
-The schedule follows the same rules as `copris_rollout_schedule` (which a test checks stage
-by stage); this module is a driver and a test vehicle, sized for small cases: it steps token
-by token from Python.
+Sized for small cases (the stand-in tables of every trajectory are resident).
 """
 from __future__ import annotations
-
-from dataclasses import dataclass, field
 
 import numpy as np
 import torch
@@ -35,235 +33,170 @@ from .runner import dtype_code, require_gpu, to_device, workspace
 from .workloads import BF16, StandInPolicy
 
 
-@dataclass
-class Trajectory:
-    tokens: list = field(default_factory=list)     # sampled token per generated position
-    logp: list = field(default_factory=list)       # its log-prob under the generating policy
-    tag: list = field(default_factory=list)        # stage that generated it (Eq. 6: pieces in stage order)
-    attn_out: list = field(default_factory=list)   # decode attention output [Hq, D] (fp32) per position
-    attn_lse: list = field(default_factory=list)   # and its log-sum-exp [Hq]
-    started: bool = False
+def _upload(a: np.ndarray, dev) -> torch.Tensor:
+    """Host array -> device through pinned memory, without waiting for the stream."""
+    return torch.from_numpy(np.ascontiguousarray(a)).pin_memory().to(dev, non_blocking=True)
+
+
+class _DeviceTables:
+    """The stand-in model of one policy version on the device: the rows of all trajectories
+    back to back, `row0[tr]` being the first row of trajectory tr."""
+
+    def __init__(self, policy: StandInPolicy, ver: int, dev):
+        n_traj = policy.resp_len.size
+        lens = [policy.length(tr) for tr in range(n_traj)]
+        self.row0_host = np.concatenate([[0], np.cumsum(lens)]).astype(np.int64)
+        cat = lambda key: to_device(np.concatenate([policy.tables(tr, ver)[key] for tr in range(n_traj)]), device=dev)
+        self.q, self.k, self.v, self.hidden = cat("q"), cat("k"), cat("v"), cat("hidden")
+        self.row0 = to_device(self.row0_host[:-1], device=dev)
+        self.weight = to_device(policy.weight(ver), device=dev)
 
 
 class RolloutLoop:
     def __init__(self, policy: StandInPolicy, pool: int, batch_inputs: int, *, sample_seed: int = 7,
                  temperature: float = 1.0, eps_low: float = 0.2, eps_high: float = 0.28,
-                 page_size: int = 16, page_seed: int = 11):
+                 page_size: int = 16, page_seed: int = 11, record: bool = True):
         self.m = policy
         self.pool, self.batch_inputs = int(pool), int(batch_inputs)
         self.sample_seed, self.temperature = int(sample_seed), float(temperature)
         self.eps_low, self.eps_high = float(eps_low), float(eps_high)
         self.page_size = int(page_size)
-        self.dev = require_gpu()
+        self.record = bool(record)
+        self.dev = dev = require_gpu()
         self.dt = dtype_code(policy.dtype)
-        self.I = int(policy.prompt_len.size)
         self.N = policy.samples
-        max_len = int((policy.prompt_len[:, None] + policy.resp_len).max())
-        self.max_pages = (max_len + page_size - 1) // page_size
-        self.num_pages = self.pool * self.max_pages + 3
+        self.n_traj = int(policy.resp_len.size)
+        self.max_resp = int(policy.resp_len.max())
+        longest = int((policy.prompt_len[:, None] + policy.resp_len).max())
+        self.num_pages = self.pool * ((longest + page_size - 1) // page_size) + 3
         # physical pages are handed out in a shuffled order, so block tables are scattered
         order = np.random.default_rng(page_seed).permutation(self.num_pages)
-        self.free_pages = [int(x) for x in order]
+        self.manager = binding.RolloutManager(policy.prompt_len, policy.resp_len, self.pool, self.batch_inputs,
+                                              page_size, num_pages=self.num_pages, page_order=order)
+        self.max_pages = self.manager.max_pages
         tdt = torch.bfloat16 if policy.dtype == BF16 else torch.float32
         shape = (self.num_pages, policy.Hkv, page_size, policy.D)
-        self.k_cache = torch.full(shape, float("nan"), dtype=tdt, device=self.dev)
-        self.v_cache = torch.full(shape, float("nan"), dtype=tdt, device=self.dev)
-        self.traj = [Trajectory() for _ in range(self.I * self.N)]
-        self.pages_of = {}                      # running trajectory -> list of physical pages
-        self.consumed = [False] * self.I
-        self.stages = []                        # per-stage dicts: stats, plan, training batch
+        self.k_cache = torch.full(shape, float("nan"), dtype=tdt, device=dev)
+        self.v_cache = torch.full(shape, float("nan"), dtype=tdt, device=dev)
+        # pool state
+        self.seq_id = torch.full((self.pool,), -1, dtype=torch.int64, device=dev)
+        self.ctx_len = torch.zeros(self.pool, dtype=torch.int32, device=dev)
+        self.step = torch.zeros(self.pool, dtype=torch.int32, device=dev)
+        self.block_table = torch.zeros((self.pool, self.max_pages), dtype=torch.int32, device=dev)
+        # the buffer: one row per trajectory
+        self.buf_token = torch.full((self.n_traj, self.max_resp), -1, dtype=torch.int32, device=dev)
+        self.buf_logp = torch.full((self.n_traj, self.max_resp), float("nan"), dtype=torch.float32, device=dev)
+        self.buf_tag = torch.full((self.n_traj, self.max_resp), -1, dtype=torch.int32, device=dev)
+        # per-step outputs
+        self.attn_out = torch.empty((self.pool, policy.Hq, policy.D), dtype=tdt, device=dev)
+        self.attn_lse = torch.empty((self.pool, policy.Hq), dtype=torch.float32, device=dev)
+        self.token = torch.empty(self.pool, dtype=torch.int32, device=dev)
+        self.logprob = torch.empty(self.pool, dtype=torch.float32, device=dev)
         self.attn_ws = workspace(binding.decode_attn_workspace_bytes(
-            self.pool, policy.Hq, policy.Hkv, policy.D, page_size, self.max_pages), self.dev)
-        self.lm_ws = workspace(binding.lmhead_logprob_workspace_bytes(self.pool, policy.H, policy.V), self.dev)
+            self.pool, policy.Hq, policy.Hkv, policy.D, page_size, self.max_pages), dev)
+        self.lm_ws = workspace(binding.lmhead_logprob_workspace_bytes(self.pool, policy.H, policy.V), dev)
+        self.stages = []
+        self.host_syncs = 0                  # times the host waited for the device
 
-    # ---- helpers -------------------------------------------------------------------------
-    def _gen(self, tr):
-        return len(self.traj[tr].tokens)
+    # ---- one decode step, all on the stream, nothing read back ---------------------------
+    def _prefill(self, plan, tab):
+        ent = plan["entered"][plan["entered"][:, 2] > 0]
+        if ent.shape[0] == 0:
+            return
+        lens = ent[:, 2].astype(np.int64)
+        rows = np.concatenate([tab.row0_host[t] + np.arange(n) for t, n in zip(ent[:, 1], lens)])
+        idx = _upload(rows, self.dev)
+        cu = _upload(np.concatenate([[0], np.cumsum(lens)]).astype(np.int32), self.dev)
+        table = self.block_table.index_select(0, _upload(ent[:, 0].astype(np.int64), self.dev))
+        q, k, v = tab.q.index_select(0, idx), tab.k.index_select(0, idx), tab.v.index_select(0, idx)
+        binding.prefill_attn(q, k, v, cu, table, self.k_cache, self.v_cache, torch.empty_like(q), None,
+                             max_seqlen=int(lens.max()), scale=self.m.scale, dtype=self.dt)
 
-    def _target(self, tr):
-        i, s = divmod(tr, self.N)
-        return int(self.m.resp_len[i, s])
+    def _decode_step(self, plan, tab, stage, log):
+        binding.rollout_apply(_upload(plan["cmds"], self.dev), plan["n_slot_cmds"], plan["n_page_cmds"],
+                              self.seq_id, self.ctx_len, self.step, self.block_table)
+        self._prefill(plan, tab)
+        # the stand-in's forward pass for the position being decoded: a row look-up
+        row = tab.row0.index_select(0, self.seq_id.clamp(min=0)) + (self.ctx_len - 1).clamp(min=0)
+        q, hidden = tab.q.index_select(0, row), tab.hidden.index_select(0, row)
+        binding.kv_append(tab.k.index_select(0, row), tab.v.index_select(0, row), self.block_table, self.ctx_len,
+                          self.k_cache, self.v_cache, dtype=self.dt)
+        binding.decode_attn(q, self.k_cache, self.v_cache, self.block_table, self.ctx_len, self.attn_out,
+                            self.attn_lse, self.attn_ws, scale=self.m.scale, dtype=self.dt)
+        binding.lmhead_logprob(hidden, tab.weight, self.seq_id, self.step, self.token, self.logprob, None,
+                               self.lm_ws, seed=self.sample_seed, temperature=self.temperature, dtype=self.dt)
+        if self.record:
+            log.append((self.attn_out.float(), self.attn_lse.clone()))
+        binding.traj_append(self.token, self.logprob, self.seq_id, self.step, self.ctx_len, stage,
+                            self.buf_token, self.buf_logp, self.buf_tag)
 
-    def _prompt(self, tr):
-        return int(self.m.prompt_len[tr // self.N])
-
-    def _ensure_pages(self, tr, n_tokens):
-        need = (n_tokens + self.page_size - 1) // self.page_size
-        pages = self.pages_of.setdefault(tr, [])
-        while len(pages) < need:
-            pages.append(self.free_pages.pop(0))
-
-    def _release(self, tr):
-        self.free_pages.extend(self.pages_of.pop(tr, []))
-
-    def _table(self, trs):
-        bt = np.zeros((len(trs), self.max_pages), dtype=np.int32)
-        for r, tr in enumerate(trs):
-            p = self.pages_of[tr]
-            bt[r, :len(p)] = p
-        return to_device(bt, device=self.dev)
-
-    def _complete_inputs(self):
-        return [i for i in range(self.I) if not self.consumed[i] and all(
-            self.traj[i * self.N + s].started and self._gen(i * self.N + s) >= self._target(i * self.N + s)
-            for s in range(self.N))]
-
-    # ---- kernels ---------------------------------------------------------------------------
-    def _prefill(self, trs, ver):
-        """Rebuild the pages of prompt + generated tokens of the requests entering the pool."""
-        lens = [self._prompt(tr) + self._gen(tr) for tr in trs]
-        for tr, n in zip(trs, lens):
-            self._ensure_pages(tr, n)
-        q = np.concatenate([self.m.tables(tr, ver)["q"][:n] for tr, n in zip(trs, lens)])
-        k = np.concatenate([self.m.tables(tr, ver)["k"][:n] for tr, n in zip(trs, lens)])
-        v = np.concatenate([self.m.tables(tr, ver)["v"][:n] for tr, n in zip(trs, lens)])
+    # ---- Eq. 8 and Eq. 2-4 on the batch that leaves ------------------------------------------
+    def _train_batch(self, st, tab, stage):
+        bt = st["batch_traj"]
+        trs, lens = bt[:, 0], bt[:, 1].astype(np.int64)
         cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
-        qd, kd, vd = (to_device(x, device=self.dev) for x in (q, k, v))
-        out = torch.empty_like(qd)
-        lse = torch.empty((qd.shape[0], self.m.Hq), dtype=torch.float32, device=self.dev)
-        binding.prefill_attn(qd, kd, vd, to_device(cu, device=self.dev), self._table(trs), self.k_cache,
-                             self.v_cache, out, lse, max_seqlen=int(max(lens)), scale=self.m.scale, dtype=self.dt)
-        return lens, lse.cpu().numpy()
-
-    def _decode_step(self, active, ver, stage):
-        pos = [self._prompt(tr) + self._gen(tr) for tr in active]
-        for tr, p in zip(active, pos):
-            self._ensure_pages(tr, p + 1)
-        # KV append of the new position (plain copies into the pages)
-        page = torch.tensor([self.pages_of[tr][p // self.page_size] for tr, p in zip(active, pos)], device=self.dev)
-        off = torch.tensor([p % self.page_size for p in pos], device=self.dev)
-        k_new = to_device(np.stack([self.m.tables(tr, ver)["k"][p] for tr, p in zip(active, pos)]), device=self.dev)
-        v_new = to_device(np.stack([self.m.tables(tr, ver)["v"][p] for tr, p in zip(active, pos)]), device=self.dev)
-        self.k_cache[page, :, off, :] = k_new
-        self.v_cache[page, :, off, :] = v_new
-        C = len(active)
-        q = to_device(np.stack([self.m.tables(tr, ver)["q"][p] for tr, p in zip(active, pos)]), device=self.dev)
-        ctx = to_device(np.asarray([p + 1 for p in pos], dtype=np.int32), device=self.dev)
-        out = torch.empty_like(q)
-        lse = torch.empty((C, self.m.Hq), dtype=torch.float32, device=self.dev)
-        binding.decode_attn(q, self.k_cache, self.v_cache, self._table(active), ctx, out, lse, self.attn_ws,
-                            scale=self.m.scale, dtype=self.dt)
-        hidden = to_device(np.stack([self.m.tables(tr, ver)["hidden"][p] for tr, p in zip(active, pos)]),
-                           device=self.dev)
-        seq_id = to_device(np.asarray(active, dtype=np.int64), device=self.dev)
-        step = to_device(np.asarray([self._gen(tr) for tr in active], dtype=np.int32), device=self.dev)
-        token = torch.empty(C, dtype=torch.int32, device=self.dev)
-        logp = torch.empty(C, dtype=torch.float32, device=self.dev)
-        llse = torch.empty(C, dtype=torch.float32, device=self.dev)
-        binding.lmhead_logprob(hidden, self.weight_dev, seq_id, step, token, logp, llse, self.lm_ws,
-                               seed=self.sample_seed, temperature=self.temperature, dtype=self.dt)
-        torch.cuda.synchronize()
-        tok, lp = token.cpu().numpy(), logp.cpu().numpy()
-        o, l = out.float().cpu().numpy(), lse.cpu().numpy()
-        for r, tr in enumerate(active):
-            t = self.traj[tr]
-            t.tokens.append(int(tok[r]))
-            t.logp.append(float(lp[r]))
-            t.tag.append(stage)
-            t.attn_out.append(o[r])
-            t.attn_lse.append(l[r])
-
-    def _train_batch(self, batch, ver, stage):
-        """Eq. 8 and Eq. 2-4 on the inputs that leave: current-policy log-probs of the buffered
-        tokens, ratios against the buffered log-probs, clipped surrogate."""
-        trs = [i * self.N + s for i in batch for s in range(self.N)]
-        lens = [self._gen(tr) for tr in trs]
-        cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
-        M = int(cu[-1])
-        hidden = np.concatenate([self.m.tables(tr, ver)["hidden"][self._prompt(tr):self._prompt(tr) + n]
-                                 for tr, n in zip(trs, lens)])
-        tokens = np.concatenate([np.asarray(self.traj[tr].tokens, dtype=np.int32) for tr in trs])
-        tags = np.concatenate([np.asarray(self.traj[tr].tag, dtype=np.int64) for tr in trs])
-        old = np.concatenate([np.asarray(self.traj[tr].logp, dtype=np.float32) for tr in trs])
-        split = np.asarray([int((np.asarray(self.traj[tr].tag) < stage).sum()) for tr in trs], dtype=np.int32)
-        # Eq. 6: a trajectory's buffer is its per-stage pieces in token order, so the tokens of
-        # earlier stages are a prefix; the side of the split that is not selected holds NaN
-        logp_buf = np.where(tags < stage, old, np.float32("nan")).astype(np.float32)
-        logp_roll = np.where(tags < stage, np.float32("nan"), old).astype(np.float32)
-        adv = np.random.default_rng([self.m.seed, 0xAD, stage]).normal(size=len(trs)).astype(np.float32)
-        dev = self.dev
-        hd, tk = to_device(hidden, device=dev), to_device(tokens, device=dev)
-        logp_cur = torch.empty(M, dtype=torch.float32, device=dev)
-        lse = torch.empty(M, dtype=torch.float32, device=dev)
-        ws = workspace(binding.lmhead_token_logprob_workspace_bytes(M, self.m.H, self.m.V, self.dt), dev)
-        binding.lmhead_token_logprob(hd, self.weight_dev, tk, logp_cur, lse, ws, temperature=self.temperature,
-                                     dtype=self.dt)
-        cud, spd = to_device(cu, device=dev), to_device(split, device=dev)
-        bufd, rolld, advd = (to_device(x, device=dev) for x in (logp_buf, logp_roll, adv))
+        M, B, dev = int(cu[-1]), len(trs), self.dev
         f = lambda n, t=torch.float32: torch.empty(n, dtype=t, device=dev)
-        ratio, clipped, seq_sum = f(M), f(M), f(len(trs))
-        seq_cnt, seq_nclip = f(len(trs), torch.int32), f(len(trs), torch.int32)
-        binding.is_ratio(logp_cur, bufd, rolld, cud, spd, None, ratio, clipped, seq_sum, seq_cnt, seq_nclip,
-                         eps_low=self.eps_low, eps_high=self.eps_high)
-        surr, grad, seq_surr, seq_cnt2, obj = f(M), f(M), f(len(trs)), f(len(trs), torch.int32), f(2)
-        binding.grpo_surrogate(logp_cur, bufd, rolld, cud, spd, None, advd, surr, grad, seq_surr, seq_cnt2, obj,
-                               eps_low=self.eps_low, eps_high=self.eps_high)
-        torch.cuda.synchronize()
+        cud, trd = _upload(cu, dev), _upload(trs.astype(np.int32), dev)
+        tokens, logp_buf, logp_roll, split = f(M, torch.int32), f(M), f(M), f(B, torch.int32)
+        binding.traj_gather(self.buf_token, self.buf_logp, self.buf_tag, trd, cud, stage, tokens, logp_buf,
+                            logp_roll, split)
+        prompt = self.m.prompt_len[trs // self.N]
+        rows = np.concatenate([tab.row0_host[t] + p + np.arange(n) for t, p, n in zip(trs, prompt, lens)])
+        hidden = tab.hidden.index_select(0, _upload(rows, dev))
+        adv_host = np.random.default_rng([self.m.seed, 0xAD, stage]).normal(size=B).astype(np.float32)
+        adv = _upload(adv_host, dev)
+        logp_cur, lse = f(M), f(M)
+        ws = workspace(binding.lmhead_token_logprob_workspace_bytes(M, self.m.H, self.m.V, self.dt), dev)
+        binding.lmhead_token_logprob(hidden, tab.weight, tokens, logp_cur, lse, ws, temperature=self.temperature,
+                                     dtype=self.dt)
+        ratio, clipped, seq_sum = f(M), f(M), f(B)
+        seq_cnt, seq_nclip = f(B, torch.int32), f(B, torch.int32)
+        binding.is_ratio(logp_cur, logp_buf, logp_roll, cud, split, None, ratio, clipped, seq_sum, seq_cnt,
+                         seq_nclip, eps_low=self.eps_low, eps_high=self.eps_high)
+        surr, grad, seq_surr, seq_cnt2, obj = f(M), f(M), f(B), f(B, torch.int32), f(2)
+        binding.grpo_surrogate(logp_cur, logp_buf, logp_roll, cud, split, None, adv, surr, grad, seq_surr,
+                               seq_cnt2, obj, eps_low=self.eps_low, eps_high=self.eps_high)
+        torch.cuda.synchronize()             # the one wait of the stage
+        self.host_syncs += 1
         g = lambda t: t.cpu().numpy()
-        return {"trajectories": trs, "cu_seqlens": cu, "split": split, "tokens": tokens, "tags": tags,
-                "hidden": hidden, "logp_buf": logp_buf, "logp_roll": logp_roll, "adv": adv,
-                "logp_cur": g(logp_cur), "ratio": g(ratio), "ratio_clipped": g(clipped), "seq_sum": g(seq_sum),
-                "seq_cnt": g(seq_cnt), "seq_nclip": g(seq_nclip), "surr": g(surr), "grad": g(grad),
-                "seq_surr": g(seq_surr), "obj_token_mean": float(g(obj)[0]), "obj_seq_mean": float(g(obj)[1])}
+        out = {"trajectories": trs.tolist(), "cu_seqlens": cu, "split": g(split), "manager_split": bt[:, 2].copy(),
+               "tokens": g(tokens), "logp_buf": g(logp_buf), "logp_roll": g(logp_roll), "adv": adv_host,
+               "logp_cur": g(logp_cur), "ratio": g(ratio), "ratio_clipped": g(clipped), "seq_sum": g(seq_sum),
+               "seq_cnt": g(seq_cnt), "seq_nclip": g(seq_nclip), "surr": g(surr), "grad": g(grad),
+               "seq_surr": g(seq_surr), "obj_token_mean": float(g(obj)[0]), "obj_seq_mean": float(g(obj)[1])}
+        if self.record:
+            tag_rows = g(self.buf_tag)
+            out["tags"] = np.concatenate([tag_rows[t, :n] for t, n in zip(trs, lens)]) if B else np.zeros(0, np.int32)
+            out["hidden"] = np.concatenate([self.m.tables(t, stage)["hidden"][p:p + n]
+                                            for t, p, n in zip(trs, prompt, lens)])
+        return out
 
-    # ---- the loop --------------------------------------------------------------------------
+    # ---- stages ------------------------------------------------------------------------------
     def run(self, max_stages: int):
-        for stage in range(max_stages):
-            ver = stage                              # one policy version per rollout stage
-            self.weight_dev = to_device(self.m.weight(ver), device=self.dev)
-            T = len(self.traj)
-            resume_q = [tr for tr in range(T) if not self.consumed[tr // self.N] and self.traj[tr].started
-                        and self._gen(tr) < self._target(tr)]
-            fresh_q = [tr for tr in range(T) if not self.traj[tr].started]
-            queue, n_resume, qpos = resume_q + fresh_q, len(resume_q), 0
-            st = {"steps": 0, "generated": 0, "slot_steps_idle": 0, "resumed": 0, "reprefill_tokens": 0,
-                  "peak_pages": 0}
-            plan = []                                # per decode step: (entered, their prefill lengths, active)
-            active = []
-            done = self._complete_inputs() if len(self._complete_inputs()) >= self.batch_inputs else None
-            while done is None:
-                entered = []
-                while len(active) < self.pool and qpos < len(queue):
-                    tr = queue[qpos]
-                    if qpos < n_resume:
-                        st["resumed"] += 1
-                        st["reprefill_tokens"] += self._prompt(tr) + self._gen(tr)
-                    qpos += 1
-                    self.traj[tr].started = True
-                    active.append(tr)
-                    entered.append(tr)
-                if not active:
+        for _ in range(max_stages):
+            stage = self.manager.begin_stage()
+            tab = _DeviceTables(self.m, stage, self.dev)        # one policy version per stage
+            plans, log = [], []
+            while True:
+                code, plan = self.manager.next_step()
+                if code != binding.ROLLOUT_STEP:
                     break
-                lens = self._prefill(entered, ver)[0] if entered else []
-                self._decode_step(active, ver, stage)
-                plan.append({"entered": list(entered), "prefill_len": list(lens), "active": list(active)})
-                st["steps"] += 1
-                st["slot_steps_idle"] += self.pool - len(active)
-                st["generated"] += len(active)
-                st["peak_pages"] = max(st["peak_pages"], sum(len(self.pages_of[tr]) for tr in active))
-                for tr in active:
-                    if self._gen(tr) >= self._target(tr):
-                        self._release(tr)
-                active = [tr for tr in active if self._gen(tr) < self._target(tr)]
-                ci = self._complete_inputs()
-                if len(ci) >= self.batch_inputs:
-                    done = ci
-            if done is None:
+                self._decode_step(plan, tab, stage, log)
+                plans.append(plan)
+            if code == binding.ROLLOUT_EXHAUSTED:
                 break
-            for tr in active:                        # paused: their pages die with the policy version
-                self._release(tr)
-            batch = done[:self.batch_inputs]
-            train = self._train_batch(batch, ver, stage)
-            tags = train["tags"]
-            st["batch_inputs"] = batch
-            st["batch_tokens"] = int(tags.size)
-            st["batch_offpolicy"] = int((tags < stage).sum())
-            st["batch_traj_offpolicy"] = int((train["split"] > 0).sum())
-            st["max_staleness"] = int((stage - tags).max()) if tags.size else 0
-            for i in batch:
-                self.consumed[i] = True
-            live = [tr for tr in range(T) if not self.consumed[tr // self.N] and self.traj[tr].started]
-            st["paused"] = sum(1 for tr in live if self._gen(tr) < self._target(tr))
-            st["buffered_complete"] = sum(1 for tr in live if self._gen(tr) >= self._target(tr))
-            self.stages.append({"stats": st, "plan": plan, "train": train, "version": ver})
+            st = self.manager.end_stage()
+            train = self._train_batch(st, tab, stage)
+            steps = [{"slot_traj": p["slot_traj"], "entered": p["entered"], "finishing": p["finishing"]}
+                     for p in plans]
+            if self.record:
+                for s, (o, l) in zip(steps, log):
+                    s["attn_out"], s["attn_lse"] = o.cpu().numpy(), l.cpu().numpy()
+            self.stages.append({"stats": {k: v for k, v in st.items() if k != "batch_traj"}, "steps": steps,
+                                "train": train, "version": stage})
         return self.stages
+
+    def buffers(self):
+        """The buffer rows as host arrays: (tokens, log-probs, stage tags), [n_traj, max_resp]."""
+        return self.buf_token.cpu().numpy(), self.buf_logp.cpu().numpy(), self.buf_tag.cpu().numpy()

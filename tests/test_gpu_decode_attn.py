@@ -116,16 +116,38 @@ def _sampled_subproblem(inp, cfg, seqs):
             "block_table": bt, "ctx_len": inp["ctx_len"][seqs], "scale": inp["scale"]}
 
 
-@pytest.mark.parametrize("k", [1, 2, 3])
-def test_full_size_configs_on_sampled_sequences(R, k):
+def _check_sequences(inp, cfg, out, lse, seqs, what, chunk=32):
+    """Oracle comparison of the given sequences, a chunk at a time (bounds the fp64 copies)."""
+    worst = 0.0
+    for i in range(0, len(seqs), chunk):
+        part = np.asarray(seqs[i:i + chunk])
+        sub = _sampled_subproblem(inp, cfg, part)
+        ref_out, ref_lse = P.oracle_attn(sub, cfg.dtype)
+        worst = max(worst, P.check_attn(out[part], lse[part], ref_out, ref_lse, cfg.dtype, f"{what} seqs {i}.."))
+    return worst
+
+
+@pytest.mark.parametrize("k", [1, 2])
+def test_full_size_configs_every_sequence(R, k):
+    # the 1.5B- and 7B-shaped steps, in the launch configuration the benchmark times:
+    # every one of the C sequences against the oracle
     cfg = W.DECODE_CONFIGS[k]
     inp = W.make_decode_inputs(cfg, with_lmhead=False)
     out, lse = R.run_decode_attn(inp, cfg.dtype)
     assert np.isfinite(out).all() and np.isfinite(lse).all()
+    _check_sequences(inp, cfg, out, lse, np.arange(cfg.C), f"cfg{k}")
+
+
+def test_long_tail_config_every_resumed_trajectory(R):
+    # C = 512: all ten 32768-token sequences, the shortest, and sixteen others
+    cfg = W.DECODE_CONFIGS[3]
+    inp = W.make_decode_inputs(cfg, with_lmhead=False)
+    out, lse = R.run_decode_attn(inp, cfg.dtype)
+    assert np.isfinite(out).all() and np.isfinite(lse).all()
     ctx = inp["ctx_len"]
-    order = np.argsort(ctx)
-    rng = np.random.default_rng(k)
-    seqs = np.unique(np.concatenate([order[:2], order[-2:], rng.choice(cfg.C, 8, replace=False)]))
-    sub = _sampled_subproblem(inp, cfg, seqs)
-    ref_out, ref_lse = P.oracle_attn(sub, cfg.dtype)
-    P.check_attn(out[seqs], lse[seqs], ref_out, ref_lse, cfg.dtype, f"cfg{k}")
+    longest = np.flatnonzero(ctx == ctx.max())
+    assert len(longest) == 10 and ctx.max() == 32768
+    rest = np.setdiff1d(np.arange(cfg.C), longest)
+    others = np.random.default_rng(3).choice(rest, 16, replace=False)
+    seqs = np.unique(np.concatenate([longest, np.argsort(ctx)[:2], others]))
+    _check_sequences(inp, cfg, out, lse, seqs, "cfg3", chunk=8)

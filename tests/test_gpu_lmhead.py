@@ -35,7 +35,7 @@ def test_small_shapes(R, dtype, C, H, V):
     inp = W.make_small_lmhead_case(C * 7 + V, C, H, V, dtype, w_std=0.05)
     tok, lp, lse = R.run_lmhead_logprob(inp, dtype)
     n_exempt = P.check_lmhead(tok, lp, lse, P.oracle_lmhead(inp, dtype), f"{dtype} {C}x{H}x{V}")
-    assert n_exempt <= max(2, C // 20)
+    assert n_exempt <= 2          # expected near-ties: about C / 1000
 
 
 def test_zero_weights_token_is_argmax_of_the_noise(R):
@@ -75,11 +75,15 @@ def test_bitwise_reproducible(R):
 
 
 @pytest.mark.parametrize("k", [1, 2])
-def test_full_size_configs_on_sampled_rows(R, k):
+def test_full_size_configs_every_row(R, k):
+    # the 1.5B- and 7B-shaped LM heads (vocabulary 151936): every one of the C rows
     cfg = W.DECODE_CONFIGS[k]
     inp = W.make_decode_inputs(cfg, with_attn=False)
     tok, lp, lse = R.run_lmhead_logprob(inp, cfg.dtype)
     assert ((0 <= tok) & (tok < cfg.V)).all() and np.isfinite(lp).all() and (lp <= 0).all()
-    rows = np.sort(np.random.default_rng(k).choice(cfg.C, 12, replace=False))
-    ref = P.oracle_lmhead(inp, cfg.dtype, rows=rows)
-    P.check_lmhead(tok[rows], lp[rows], lse[rows], ref, f"cfg{k}")
+    exempt = 0
+    for r0 in range(0, cfg.C, 64):            # 64 rows of full log-softmax at a time (78 MB in fp64)
+        rows = np.arange(r0, min(r0 + 64, cfg.C))
+        ref = P.oracle_lmhead(inp, cfg.dtype, rows=rows)
+        exempt += P.check_lmhead(tok[rows], lp[rows], lse[rows], ref, f"cfg{k} rows {r0}..")
+    assert exempt <= 2

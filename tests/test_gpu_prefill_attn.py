@@ -44,15 +44,19 @@ def test_large_scores_move_the_softmax_reference_often(R, gain):
     ramp = np.linspace(0.0, 3.0, q.shape[0], dtype=np.float32)[:, None]
     q[:, 3, :] = ramp * np.sign(W.bf16_bits_to_f32(b["k"])[:, 0, :]).astype(np.float32)
     b["q"] = W.f32_to_bf16_bits(q)
+    # nearly one-hot rows return single V rows; with |v| up to 5 half a bf16 ulp of the stored
+    # output alone would be 1.6e-2, so the values are scaled to |v| < 1.3 (half an ulp 3.9e-3)
+    # and the same absolute bar as everywhere else applies
+    b["v"] = W.f32_to_bf16_bits(W.bf16_bits_to_f32(b["v"]) * 0.25)
     out, lse, kc, vc = R.run_prefill_attn(b, W.BF16)
     ref_out, ref_lse, ref_kc, ref_vc = P.oracle_prefill(b, W.BF16)
     assert np.isfinite(out).all() and np.isfinite(lse).all()
-    # nearly one-hot rows return single V rows (|v| up to 4-5), where half a bf16 ulp of the
-    # stored output alone is 1.6e-2: the bound scales with the reference here
-    err = np.abs(out.astype(np.float64) - ref_out)
-    assert (err <= 1e-2 + 1e-2 * np.abs(ref_out)).all(), f"gain {gain}: worst {err.max():.3e}"
+    err = np.abs(out.astype(np.float64) - ref_out).max()
+    assert err <= P.ATTN_TOL[W.BF16], f"gain {gain}: worst {err:.3e}"
+    # scores reach several hundred here: fp32 accumulation of a 128-term dot product of that
+    # size carries ~1e-7 of it, so the log-sum-exp bound has a relative part
     lerr = np.abs(lse.astype(np.float64) - ref_lse)
-    assert (lerr <= 2e-3 + 1e-4 * np.abs(ref_lse)).all(), f"gain {gain}: lse worst {lerr.max():.3e}"
+    assert (lerr <= P.ATTN_LSE_TOL[W.BF16] + 1e-4 * np.abs(ref_lse)).all(), f"gain {gain}: lse worst {lerr.max():.3e}"
     np.testing.assert_array_equal(kc, ref_kc)
     np.testing.assert_array_equal(vc, ref_vc)
 

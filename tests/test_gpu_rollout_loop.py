@@ -1,10 +1,12 @@
-"""GPU: the fixed-concurrency rollout loop end to end (Section 4) against the oracle.
+"""GPU: rollout stages under the library's rollout manager, end to end (Section 4), against the
+oracle.
 
-The loop (product code) drives prefill, KV pages, decode attention, sampling, the log-prob
-buffer with its stage tags (Eq. 6), early termination, resumption under a new policy version,
-and Eq. 8 / Eq. 2-4 on every training batch.  The test replays the loop's recorded plan with
+The loop (product code) asks the manager for every decision and keeps the pool state and the
+buffer of partial trajectories (Eq. 6) on the device; it drives prefill, KV pages, KV append,
+decode attention, sampling, the buffer, early termination, resumption under a new policy
+version, and Eq. 8 / Eq. 2-4 on every training batch.  The test replays the recorded steps with
 the oracle's functions on the same seeded stand-in inputs, and checks the stage statistics
-against the library's scheduler and the oracle's token-by-token simulation.
+against the oracle's token-by-token simulation (an independent implementation of the rules).
 """
 import numpy as np
 import pytest
@@ -37,26 +39,28 @@ STAT_KEYS = ("steps", "generated", "slot_steps_idle", "batch_tokens", "batch_off
              "max_staleness", "resumed", "reprefill_tokens", "paused", "buffered_complete", "peak_pages")
 
 
-def test_the_schedule_is_the_schedulers(run):
+def test_the_schedule_is_the_oracles(run):
     from paper_2511_05589_amd import binding
-    _, _, stages = run
-    lib = binding.rollout_schedule(PROMPT, RESP, POOL, BATCH, max_stages=3)
+    _, loop, stages = run
     ora = O.rollout_schedule(PROMPT, RESP, POOL, BATCH, max_stages=3)
-    assert len(stages) == len(lib) == len(ora) == 3
+    lib = binding.rollout_schedule(PROMPT, RESP, POOL, BATCH, max_stages=3)
+    assert len(stages) == len(ora) == 3
     for k, st in enumerate(stages):
         for key in STAT_KEYS:
-            assert st["stats"][key] == lib[k][key] == ora[k][key], (k, key)
-        assert st["stats"]["batch_inputs"] == lib[k]["batch_inputs"][:BATCH] == ora[k]["batch_inputs"]
+            assert st["stats"][key] == ora[k][key] == lib[k][key], (k, key)
+        assert st["stats"]["batch_inputs"] == ora[k]["batch_inputs"]
+        assert st["stats"]["steps"] == len(st["steps"])
     # the case is built so that the concurrency mechanics all occur
     assert sum(st["stats"]["resumed"] for st in stages) > 0
     assert sum(st["stats"]["batch_offpolicy"] for st in stages) > 0
+    # the host waited for the device once per stage, not once per token
+    assert loop.host_syncs == len(stages) < sum(len(st["steps"]) for st in stages)
 
 
 def test_every_page_comes_back(run):
     _, loop, _ = run
     # inputs that never left keep no pages either: pages belong to running requests only
-    assert not loop.pages_of
-    assert sorted(loop.free_pages) == list(range(loop.num_pages))
+    assert loop.manager.free_pages() == loop.num_pages
 
 
 def _dense_attn(policy, tr, p, ver):
@@ -77,37 +81,54 @@ def _dense_attn(policy, tr, p, ver):
 
 def test_replay_with_the_oracle(run):
     policy, loop, stages = run
-    gen = [0] * len(loop.traj)
+    buf_token, buf_logp, buf_tag = loop.buffers()
+    gen = [0] * loop.n_traj
+    ora_buf = {}
     exempt = 0
     for k, st in enumerate(stages):
         ver = st["version"]
         w = W.to_f32(policy.weight(ver), policy.dtype)
-        for step in st["plan"]:
-            for tr, n in zip(step["entered"], step["prefill_len"]):
-                assert n == PROMPT[tr // 2] + gen[tr]          # prompt + what the buffer holds
-            for tr in step["active"]:
+        for step in st["steps"]:
+            for slot, tr, n, resumed in step["entered"]:
+                assert n == PROMPT[tr // 2] + gen[tr] and resumed == (gen[tr] > 0)   # prompt + what the buffer holds
+            for slot, tr in enumerate(step["slot_traj"]):
+                if tr < 0:
+                    continue
                 g = gen[tr]
                 p = PROMPT[tr // 2] + g
-                t = loop.traj[tr]
-                assert t.tag[g] == k
+                assert buf_tag[tr, g] == k
                 # attention over pages that prefill and the appends built (a wrong page or a
                 # stale version would show here)
                 ref_out, ref_lse = _dense_attn(policy, tr, p, ver)
-                P.check_attn(t.attn_out[g][None], t.attn_lse[g][None], ref_out, ref_lse, policy.dtype,
-                             f"stage {k} traj {tr} pos {p}")
+                P.check_attn(step["attn_out"][slot][None], step["attn_lse"][slot][None], ref_out, ref_lse,
+                             policy.dtype, f"stage {k} traj {tr} pos {p}")
                 h = W.to_f32(policy.tables(tr, ver)["hidden"][p:p + 1], policy.dtype)
                 ref = O.lmhead_logprob(h, w, np.asarray([tr]), np.asarray([g]), SAMPLE_SEED, 1.0, return_full=True)
-                tok = int(t.tokens[g])
+                tok = int(buf_token[tr, g])
                 if tok != int(ref["token"][0]):
                     assert ref["best"][0] - ref["runner_up"][0] < P.NEAR_TIE and tok == int(ref["second_token"][0])
                     exempt += 1
-                assert abs(t.logp[g] - ref["logp"][0, tok]) <= P.LOGPROB_TOL
+                assert abs(buf_logp[tr, g] - ref["logp"][0, tok]) <= P.LOGPROB_TOL
+                O.buffer_append(ora_buf, tr, k, tok, ref["logp"][0, tok])
                 gen[tr] += 1
+        # the batch of the stage is Eq. 6's concatenation of the oracle's own buffer
+        tr_ = st["train"]
+        cat = O.buffer_concat(ora_buf, tr_["trajectories"], k)
+        np.testing.assert_array_equal(tr_["cu_seqlens"], cat["cu_seqlens"])
+        np.testing.assert_array_equal(tr_["tokens"], cat["tokens"])
+        np.testing.assert_array_equal(tr_["split"], cat["split"])
+        np.testing.assert_array_equal(tr_["manager_split"], cat["split"])
+        for key in ("logp_buf", "logp_roll"):
+            np.testing.assert_array_equal(np.isnan(tr_[key]), np.isnan(cat[key]))
+            fin = ~np.isnan(cat[key])
+            assert np.abs(tr_[key][fin] - cat[key][fin]).max(initial=0.0) <= P.LOGPROB_TOL
     assert exempt <= 2
-    # every trajectory that started stopped at its length or was left paused; tags never decrease
-    for tr, t in enumerate(loop.traj):
-        assert len(t.tokens) == gen[tr] <= RESP[tr // 2][tr % 2]
-        assert all(a <= b for a, b in zip(t.tag, t.tag[1:]))
+    # every trajectory that started stopped at its length or was left paused; tags never decrease;
+    # rows past what was generated were never written
+    for tr in range(loop.n_traj):
+        assert gen[tr] <= RESP[tr // 2][tr % 2]
+        assert (np.diff(buf_tag[tr, :gen[tr]]) >= 0).all()
+        assert (buf_token[tr, gen[tr]:] == -1).all() and (buf_tag[tr, gen[tr]:] == -1).all()
 
 
 def test_training_batches(run):
@@ -133,7 +154,41 @@ def test_training_batches(run):
             saw_offpolicy = True
             assert np.abs(tr["ratio"][~on] - 1.0).max() > 1e-2
         # the split is the count of earlier-stage tokens, which Eq. 6 makes a prefix
-        for s, trj in enumerate(tr["trajectories"]):
-            tags = np.asarray(loop.traj[trj].tag)
+        cu = tr["cu_seqlens"]
+        for s in range(len(tr["trajectories"])):
+            tags = tr["tags"][cu[s]:cu[s + 1]]
             assert (tags[:tr["split"][s]] < k).all() and (tags[tr["split"][s]:] == k).all()
     assert saw_offpolicy
+
+
+def test_a_larger_pool_follows_the_oracle_schedule():
+    # pool of 64 slots, 4 samples per input: statistics only (the oracle's simulation is the
+    # reference; nothing of the loop's own is compared with itself)
+    from paper_2511_05589_amd import runner
+    from paper_2511_05589_amd.rollout_loop import RolloutLoop
+    runner.require_gpu()
+    rng = np.random.default_rng(21)
+    I, N, pool, B = 28, 4, 64, 6
+    prompt = rng.integers(4, 60, size=I)
+    resp = np.minimum(np.maximum(np.rint(rng.lognormal(3.0, 0.9, size=(I, N))), 1), 120).astype(np.int64)
+    policy = W.StandInPolicy(9, prompt, resp, dtype=W.BF16, **DIMS)
+    loop = RolloutLoop(policy, pool, B, sample_seed=3, record=False)
+    stages = loop.run(max_stages=3)
+    ora = O.rollout_schedule(prompt, resp, pool, B, max_stages=3)
+    assert len(stages) == len(ora) == 3
+    for k, st in enumerate(stages):
+        for key in STAT_KEYS:
+            assert st["stats"][key] == ora[k][key], (k, key)
+        assert st["stats"]["batch_inputs"] == ora[k]["batch_inputs"]
+        # the device's stage tags give the same stage boundaries as the manager's bookkeeping
+        np.testing.assert_array_equal(st["train"]["split"], st["train"]["manager_split"])
+        assert int(st["train"]["split"].sum()) == ora[k]["batch_offpolicy"]
+    assert sum(st["stats"]["resumed"] for st in stages) > 0
+    assert loop.host_syncs == 3 and loop.manager.free_pages() == loop.num_pages
+    # what the buffer holds is what was generated: per trajectory a prefix of valid tokens
+    buf_token, buf_logp, buf_tag = loop.buffers()
+    n_tok = (buf_tag >= 0).sum(axis=1)
+    assert int(n_tok.sum()) == sum(s["generated"] for s in ora)
+    for tr in range(loop.n_traj):
+        assert (buf_tag[tr, :n_tok[tr]] >= 0).all() and (buf_token[tr, :n_tok[tr]] >= 0).all()
+        assert np.isfinite(buf_logp[tr, :n_tok[tr]]).all() and (buf_logp[tr, :n_tok[tr]] <= 0).all()

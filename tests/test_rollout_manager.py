@@ -77,3 +77,145 @@ def test_bad_arguments():
         binding.rollout_schedule([1], [[0]], pool=1, batch_inputs=1)     # a response needs a token
     with pytest.raises(binding.CoprisError):
         binding.rollout_schedule([1], [[3]], pool=0, batch_inputs=1)
+
+
+# ---- the stepwise manager (copris_rollout_create / begin_stage / next_step / stop / end_stage) ----
+def drive(p, r, pool, B, page_size=16, max_stages=None, stop_at=None, page_seed=None):
+    """Runs the stepwise manager to the end with a numpy mirror of the pool state that only
+    the manager's commands and the per-step advance touch.  stop_at: true lengths reported
+    through copris_rollout_stop while the manager was created with `r` as upper bounds."""
+    p, r = np.asarray(p), np.asarray(r)
+    I, N = r.shape
+    order = None
+    max_pages = (int((p[:, None] + r).max()) + page_size - 1) // page_size
+    num_pages = pool * max_pages + 5
+    if page_seed is not None:
+        order = np.random.default_rng(page_seed).permutation(num_pages)
+    m = binding.RolloutManager(p, r, pool, B, page_size, num_pages=num_pages, page_order=order)
+    assert m.max_pages == max_pages
+    seq_id, ctx, step = np.full(pool, -1), np.zeros(pool, int), np.zeros(pool, int)
+    table = np.zeros((pool, max_pages), int)
+    gen = np.zeros(I * N, int)
+    stages = []
+    while max_stages is None or len(stages) < max_stages:
+        k = m.begin_stage()
+        assert k == len(stages)
+        steps = []
+        while True:
+            code, plan = m.next_step()
+            if code != binding.ROLLOUT_STEP:
+                break
+            O.pool_commands_apply(plan["cmds"], plan["n_slot_cmds"], plan["n_page_cmds"], seq_id, ctx, step, table)
+            act = plan["slot_traj"] >= 0
+            # the mirror, driven by commands only, is what the manager says is in the slots
+            assert (seq_id[act] == plan["slot_traj"][act]).all() and (ctx[~act] == 0).all()
+            assert plan["n_active"] == act.sum()
+            tr = plan["slot_traj"][act]
+            assert len(set(tr.tolist())) == len(tr)
+            assert (step[act] == gen[tr]).all() and (ctx[act] == p[tr // N] + gen[tr] + 1).all()
+            for slot, t, n_prefill, resumed in plan["entered"]:
+                assert plan["slot_traj"][slot] == t and n_prefill == p[t // N] + gen[t] and resumed == (gen[t] > 0)
+            # pages: the mirror's table equals the manager's; live pages are distinct
+            live = [table[s, j] for s in np.flatnonzero(act) for j in range((ctx[s] + page_size - 1) // page_size)]
+            assert len(set(live)) == len(live) and all(0 <= x < num_pages for x in live)
+            for s in np.flatnonzero(act):
+                n = (ctx[s] + page_size - 1) // page_size
+                assert (table[s, :n] == plan["block_table"][s, :n]).all()
+            assert m.free_pages() + len(live) - sum(
+                (ctx[s] + page_size - 1) // page_size for s in plan["finishing"]) == num_pages
+            # the step: every running request generates one token
+            gen[tr] += 1
+            step[act] += 1
+            ctx[act] += 1
+            fin = sorted(plan["finishing"].tolist())
+            assert fin == sorted(s for s in np.flatnonzero(act) if gen[plan["slot_traj"][s]] >= r.reshape(-1)[plan["slot_traj"][s]])
+            if stop_at is not None:
+                eos = [s for s in np.flatnonzero(act) if gen[plan["slot_traj"][s]] == np.asarray(stop_at).reshape(-1)[plan["slot_traj"][s]]]
+                m.stop(eos)
+            steps.append(plan)
+        if code == binding.ROLLOUT_EXHAUSTED:
+            break
+        st = m.end_stage()
+        st["plan"] = steps
+        assert m.free_pages() == num_pages              # pages belong to running requests only
+        stages.append(st)
+    m.close()
+    return stages
+
+
+def test_stepwise_hand_worked_example():
+    p, r = [10, 20, 30], [[2, 5], [3, 1], [4, 2]]
+    got = drive(p, r, pool=3, B=1)
+    _same(got, O.rollout_schedule(p, r, pool=3, batch_inputs=1))
+    # stage 1 trains on input 0: (0,0) finished in stage 0 -> all 2 tokens are earlier pieces;
+    # (0,1) had 3 of its 5 when it was paused
+    assert got[1]["batch_traj"].tolist() == [[0, 2, 2], [1, 5, 3]]
+    assert [e.tolist() for e in got[1]["plan"][0]["entered"]] == [[0, 1, 13, 1], [1, 4, 30, 0], [2, 5, 30, 0]]
+
+
+@pytest.mark.parametrize("seed", range(10))
+def test_stepwise_random_schedules(seed):
+    rng = np.random.default_rng(100 + seed)
+    I, N = int(rng.integers(1, 24)), int(rng.integers(1, 6))
+    p = rng.integers(0, 50, size=I)
+    r = np.minimum(np.maximum(np.rint(rng.lognormal(2.5, 1.0, size=(I, N))), 1), 150).astype(np.int64)
+    pool = int(rng.integers(1, 2 * I * N + 2))
+    B = int(rng.integers(1, I + 1))
+    ps = int(rng.choice([1, 16]))
+    got = drive(p, r, pool, B, page_size=ps, page_seed=seed)
+    ref = O.rollout_schedule(p, r, pool, B, page_size=ps)
+    _same(got, ref)
+    _same(got, binding.rollout_schedule(p, r, pool, B, page_size=ps))
+    for st in got:
+        bt = st["batch_traj"]
+        assert bt[:, 1].sum() == st["batch_tokens"] and bt[:, 2].sum() == st["batch_offpolicy"]
+        assert (bt[:, 0] // N).tolist() == np.repeat(st["batch_inputs"], N).tolist()
+
+
+def test_stepwise_large_pool():
+    rng = np.random.default_rng(7)
+    I, N, pool, B = 40, 8, 96, 8
+    p = rng.integers(20, 200, size=I)
+    r = np.minimum(np.maximum(np.rint(rng.lognormal(3.5, 1.0, size=(I, N))), 1), 400).astype(np.int64)
+    got = drive(p, r, pool, B, page_seed=3)
+    _same(got, O.rollout_schedule(p, r, pool, B))
+    assert len(got) == 5 and sum(s["resumed"] for s in got) > 0 and max(s["paused"] for s in got) <= pool - 1
+
+
+def test_end_of_sequence_reports_shorten_trajectories():
+    # the manager knows upper bounds only; the caller reports the real ends one by one
+    rng = np.random.default_rng(11)
+    I, N = 9, 3
+    p = rng.integers(1, 30, size=I)
+    true = rng.integers(1, 40, size=(I, N))
+    cap = true + rng.integers(0, 25, size=(I, N))
+    got = drive(p, cap, pool=7, B=2, stop_at=true)
+    ref = O.rollout_schedule(p, true, 7, 2)
+    keys = [k for k in KEYS if k != "peak_pages"]
+    assert len(got) == len(ref)
+    for g, x in zip(got, ref):
+        for key in keys:
+            assert g[key] == x[key], key
+        assert g["peak_pages"] == x["peak_pages"]
+
+
+def test_stepwise_bad_arguments_and_protocol():
+    with pytest.raises(binding.CoprisError):
+        binding.RolloutManager([1], [[0]], 1, 1)                      # a response needs a token
+    with pytest.raises(binding.CoprisError):
+        binding.RolloutManager([100], [[50]], 4, 1, num_pages=4 * 9)  # a full-length pool needs 4 * 10 pages
+    with pytest.raises(binding.CoprisError):
+        binding.RolloutManager([1], [[3]], 1, 1, num_pages=4, page_order=[0, 1, 1, 3])   # not a permutation
+    m = binding.RolloutManager([1], [[3]], 1, 1)
+    with pytest.raises(binding.CoprisError):
+        m.next_step()                                                 # no stage open
+    assert m.begin_stage() == 0
+    with pytest.raises(binding.CoprisError):
+        m.begin_stage()
+    with pytest.raises(binding.CoprisError):
+        m.end_stage()                                                 # the batch is not complete yet
+    for _ in range(3):
+        assert m.next_step()[0] == binding.ROLLOUT_STEP
+    assert m.next_step()[0] == binding.ROLLOUT_STAGE_END
+    assert m.end_stage()["batch_tokens"] == 3
+    assert m.begin_stage() == 1 and m.next_step()[0] == binding.ROLLOUT_EXHAUSTED
