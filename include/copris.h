@@ -200,6 +200,32 @@ int copris_lmhead_logprob(const void* hidden, const void* weight,
                           int C, int H, int V, int dtype, void* stream);
 
 /* ------------------------------------------------------------------------
+ * copris_lmhead_logprob for callers that cannot allocate device memory or carry a
+ * workspace: code under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  Same arguments and results as copris_lmhead_logprob, without the
+ * workspace: the per-(row, part) partials go to a static device array of the library
+ * (copris_lmhead_logprob_noalloc_max_bytes() bytes, 4 MiB; each GPU the library is
+ * used on holds one until the process ends).  The call allocates nothing and frees
+ * nothing.  The device that `stream` belongs to must be the current device.
+ *
+ * A shape that needs more partials than the array holds returns COPRIS_EWORKSPACE (the
+ * text of copris_last_error_detail() gives the sizes) and enqueues nothing.  The need
+ * is C x parts x 20 bytes: for bf16 with H % 64 == 0, parts = min(512 / ceil(C / 256),
+ * ceil(V / 128)), at most 2.6 MB for any C up to 200 000; for other shapes parts =
+ * ceil(V / 64), e.g. C <= 88 at V = 151 936.
+ * All calls on one GPU share that GPU's array: calls that overlap in time on one GPU
+ * (different streams, or threads) race.  Nothing in it needs clearing between calls:
+ * every partial a call reads it has written first.
+ * ------------------------------------------------------------------------ */
+size_t copris_lmhead_logprob_noalloc_max_bytes(void);
+
+int copris_lmhead_logprob_noalloc(const void* hidden, const void* weight,
+                                  const int64_t* seq_id, const int32_t* step,
+                                  uint64_t seed, float temperature,
+                                  int32_t* token, float* logprob, float* lse,
+                                  int C, int H, int V, int dtype, void* stream);
+
+/* ------------------------------------------------------------------------
  * Log-probability of GIVEN tokens under the current policy (teacher forcing).
  *
  * Section 4, "Cross-stage Importance Sampling Correction": the log-probs of the

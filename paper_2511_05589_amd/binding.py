@@ -35,6 +35,9 @@ SIGNATURES = {
     "copris_lmhead_logprob_workspace_bytes": (c_size_t, [c_int] * 3),
     "copris_lmhead_logprob": (c_int, [c_void_p] * 4 + [c_uint64, c_float] + [c_void_p] * 4
                               + [c_size_t] + [c_int] * 4 + [c_void_p]),
+    "copris_lmhead_logprob_noalloc_max_bytes": (c_size_t, []),
+    "copris_lmhead_logprob_noalloc": (c_int, [c_void_p] * 4 + [c_uint64, c_float] + [c_void_p] * 3
+                                      + [c_int] * 4 + [c_void_p]),
     "copris_lmhead_token_logprob_workspace_bytes": (c_size_t, [c_int] * 4),
     "copris_lmhead_token_logprob": (c_int, [c_void_p] * 3 + [c_float] + [c_void_p] * 3 + [c_size_t]
                                     + [c_int] * 4 + [c_void_p]),
@@ -86,7 +89,7 @@ _lib = None
 class CoprisError(RuntimeError):
     def __init__(self, code: int, where: str):
         self.code = code
-        detail = load_library().copris_last_error_detail().decode() if code == COPRIS_ELAUNCH else ""
+        detail = load_library().copris_last_error_detail().decode() if code in (COPRIS_ELAUNCH, COPRIS_EWORKSPACE) else ""
         super().__init__(f"{where}: {strerror(code)} (code {code}) {detail}".rstrip())
 
 
@@ -216,6 +219,22 @@ def lmhead_logprob(hidden, weight, seq_id, step, token, logprob, lse, workspace,
         float(temperature), _ptr(token), _ptr(logprob), _ptr(lse), _ptr(workspace),
         workspace.numel() * workspace.element_size(), C, H, V, int(dtype), _stream(stream, hidden))
     _check(code, "copris_lmhead_logprob")
+
+
+def lmhead_logprob_noalloc(hidden, weight, seq_id, step, token, logprob, lse, *, seed: int,
+                           temperature: float, dtype: int, stream=None) -> None:
+    """copris_lmhead_logprob_noalloc on device tensors (partials in the library's static array)."""
+    e = _elem(dtype)
+    _expect(hidden, e, "hidden"); _expect(weight, e, "weight"); _expect(seq_id, "int64", "seq_id")
+    _expect(step, "int32", "step"); _expect(token, "int32", "token"); _expect(logprob, "float32", "logprob")
+    _expect(lse, "float32", "lse", optional=True)
+    C, H = hidden.shape
+    V = weight.shape[0]
+    code = load_library().copris_lmhead_logprob_noalloc(
+        _ptr(hidden), _ptr(weight), _ptr(seq_id), _ptr(step), int(seed) & 0xFFFFFFFFFFFFFFFF,
+        float(temperature), _ptr(token), _ptr(logprob), _ptr(lse), C, H, V, int(dtype),
+        _stream(stream, hidden))
+    _check(code, "copris_lmhead_logprob_noalloc")
 
 
 def is_ratio(logp_cur, logp_buf, logp_roll, cu_seqlens, split, mask, ratio, ratio_clipped,

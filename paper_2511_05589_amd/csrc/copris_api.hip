@@ -41,6 +41,9 @@ bool launch_ok(const char* kernel_name) {
            hipGetErrorString(e));
   return false;
 }
+void set_error_detail(const char* what, hipError_t e) {
+  snprintf(g_detail, sizeof(g_detail), "%s: %s (%s)", what, hipGetErrorName(e), hipGetErrorString(e));
+}
 void launch_hook(const char* kernel_name, int phase, hipStream_t stream) {
   if (g_hook != nullptr) g_hook(kernel_name, phase, static_cast<void*>(stream), g_hook_user);
 }
@@ -145,6 +148,33 @@ int copris_lmhead_logprob(const void* hidden, const void* weight, const int64_t*
   return copris::launch_lmhead_logprob(hidden, weight, seq_id, step, seed, temperature, token, logprob,
                                 lse, workspace, C, H, V, dtype, static_cast<hipStream_t>(stream));
 }
+
+int copris_lmhead_logprob_noalloc(const void* hidden, const void* weight, const int64_t* seq_id,
+                                  const int32_t* step, uint64_t seed, float temperature,
+                                  int32_t* token, float* logprob, float* lse, int C, int H, int V,
+                                  int dtype, void* stream) {
+  if (!hidden || !weight || !seq_id || !step || !token || !logprob) return COPRIS_EINVAL;
+  if (C <= 0 || H <= 0 || V <= 0) return COPRIS_EINVAL;
+  if (!(temperature > 0.0f) || !(temperature < INFINITY)) return COPRIS_EINVAL;
+  if (dtype != COPRIS_F32 && dtype != COPRIS_BF16) return COPRIS_EUNSUPPORTED;
+  if (H % (dtype == COPRIS_BF16 ? 8 : 4) != 0) return COPRIS_EINVAL;
+  if (!aligned16(hidden) || !aligned16(weight) || !aligned16(seq_id) || !aligned16(step) ||
+      !aligned16(token) || !aligned16(logprob) || (lse && !aligned16(lse)))
+    return COPRIS_EINVAL;
+  if (copris::lm_noalloc_scratch_needed(C, H, V, dtype) > copris::lm_noalloc_scratch_limit()) {
+    snprintf(g_detail, sizeof(g_detail),
+             "copris_lmhead_logprob_noalloc: C=%d H=%d V=%d needs %zu bytes of partials, the static "
+             "array holds %zu", C, H, V, copris::lm_noalloc_scratch_needed(C, H, V, dtype),
+             copris::lm_noalloc_scratch_limit());
+    return COPRIS_EWORKSPACE;
+  }
+  (void)hipGetLastError();
+  return copris::launch_lmhead_logprob_noalloc(hidden, weight, seq_id, step, seed, temperature, token,
+                                               logprob, lse, C, H, V, dtype,
+                                               static_cast<hipStream_t>(stream));
+}
+
+size_t copris_lmhead_logprob_noalloc_max_bytes(void) { return copris::lm_noalloc_scratch_limit(); }
 
 size_t copris_lmhead_token_logprob_workspace_bytes(int M, int H, int V, int dtype) {
   if (M <= 0 || H <= 0 || V <= 0 || (dtype != COPRIS_F32 && dtype != COPRIS_BF16)) return 0;

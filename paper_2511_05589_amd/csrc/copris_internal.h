@@ -9,6 +9,8 @@ namespace copris {
 // Checks hipGetLastError() after a launch; on failure records "<kernel>: <hip error>" for
 // copris_last_error_detail() and returns false.
 bool launch_ok(const char* kernel_name);
+// Records "<what>: <hip error>" for copris_last_error_detail().
+void set_error_detail(const char* what, hipError_t e);
 // Calls the profiling hook (if one is set) before (phase 0) / after (phase 1) a launch.
 void launch_hook(const char* kernel_name, int phase, hipStream_t stream);
 constexpr int kErrLaunch = -4;   // COPRIS_ELAUNCH
@@ -67,6 +69,14 @@ int launch_lmhead_logprob(const void* hidden, const void* weight, const int64_t*
                           const int32_t* step, uint64_t seed, float temperature, int32_t* token,
                           float* logprob, float* lse, void* workspace, int C, int H, int V,
                           int dtype, hipStream_t stream);
+
+// the sampling call with its partials in the library's own static device array
+size_t lm_noalloc_scratch_limit();
+size_t lm_noalloc_scratch_needed(int C, int H, int V, int dtype);
+int launch_lmhead_logprob_noalloc(const void* hidden, const void* weight, const int64_t* seq_id,
+                                  const int32_t* step, uint64_t seed, float temperature,
+                                  int32_t* token, float* logprob, float* lse, int C, int H, int V,
+                                  int dtype, hipStream_t stream);
 
 // ---- IS ratio ---------------------------------------------------------------
 int launch_is_ratio(const float* logp_cur, const float* logp_buf, const float* logp_roll,

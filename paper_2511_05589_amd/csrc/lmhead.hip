@@ -9,6 +9,7 @@
 // and a merge kernel combines the partials of a row: lse = m + ln s,
 // logprob = z_best - lse.  Ties on the perturbed score go to the lowest index, in
 // the tiles and in the merge, so the result does not depend on the tiling.
+#include <mutex>
 #include <type_traits>
 
 #include "copris_device.h"
@@ -958,6 +959,56 @@ int launch_lmhead_logprob(const void* hidden, const void* weight, const int64_t*
                           int dtype, hipStream_t stream) {
   return launch_lmhead(hidden, weight, seq_id, step, nullptr, seed, temperature, token, logprob, lse,
                        workspace, C, H, V, dtype, stream);
+}
+
+// --------------------------------------------------------------------------
+// The sampling call for callers that cannot allocate: the per-(row, part) partials live in a
+// file-scope device array instead of a caller workspace.  Every GPU the library runs on holds
+// its own copy of the array at its own address; the address is looked up once per device.
+// --------------------------------------------------------------------------
+constexpr size_t kLmScratchBytes = 4u << 20;
+static __device__ __align__(256) unsigned char scratch[kLmScratchBytes];
+
+size_t lm_noalloc_scratch_limit() { return kLmScratchBytes; }
+
+size_t lm_noalloc_scratch_needed(int C, int H, int V, int dtype) {
+  return static_cast<size_t>(C) * lm_parts(C, H, V, dtype, false) * sizeof(LmPartial);
+}
+
+// Device address of this GPU's copy of `scratch` (nullptr + *err set on failure).
+static void* lm_scratch_on_current_device(hipError_t* err) {
+  constexpr int kMaxDevices = 64;
+  static std::mutex mu;
+  static void* ptrs[kMaxDevices] = {};
+  int dev = -1;
+  *err = hipGetDevice(&dev);
+  if (*err != hipSuccess) return nullptr;
+  if (dev < 0 || dev >= kMaxDevices) {
+    *err = hipErrorInvalidDevice;
+    return nullptr;
+  }
+  std::lock_guard<std::mutex> lock(mu);
+  if (ptrs[dev] == nullptr) {
+    void* p = nullptr;
+    *err = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (*err != hipSuccess) return nullptr;
+    ptrs[dev] = p;
+  }
+  return ptrs[dev];
+}
+
+int launch_lmhead_logprob_noalloc(const void* hidden, const void* weight, const int64_t* seq_id,
+                                  const int32_t* step, uint64_t seed, float temperature,
+                                  int32_t* token, float* logprob, float* lse, int C, int H, int V,
+                                  int dtype, hipStream_t stream) {
+  hipError_t err = hipSuccess;
+  void* ws = lm_scratch_on_current_device(&err);
+  if (ws == nullptr) {
+    set_error_detail("hipGetSymbolAddress(scratch)", err);
+    return kErrLaunch;
+  }
+  return launch_lmhead(hidden, weight, seq_id, step, nullptr, seed, temperature, token, logprob, lse, ws,
+                       C, H, V, dtype, stream);
 }
 
 int launch_lmhead_token_logprob(const void* hidden, const void* weight, const int32_t* tokens,
