@@ -33,9 +33,10 @@
  *     synchronises and never copies to the host: every call only enqueues
  *     kernels on `stream` (a hipStream_t passed as void*; NULL = the null
  *     stream) and returns.
- *   - Outputs are fully overwritten; inputs are never modified.  No global
- *     state besides the profiling hook: calls are re-entrant across streams given
- *     disjoint workspaces and outputs.
+ *   - Outputs are fully overwritten; inputs are never modified.  The only global
+ *     state is the profiling hook (process-wide) and the static array of
+ *     copris_lmhead_logprob_noalloc: every other call is re-entrant across streams
+ *     given disjoint workspaces and outputs.
  *   - Tensors are dense, row-major, last index fastest, and their base
  *     addresses must be 16-byte aligned.
  *   - dtype: COPRIS_F32 (0) or COPRIS_BF16 (1).  bf16 tensors accumulate in fp32.
@@ -95,9 +96,13 @@ void copris_set_launch_hook(copris_launch_hook_fn hook, void* user);
  *     out[i][h][:] = sum_t softmax(s)_t * v_cache[page][kvh][slot][:]
  *     lse[i][h]    = log sum_t exp(s_t)
  *
- * Work is split along the context (fixed-size token chunks, merged in chunk
- * order), so a few very long resumed trajectories do not serialise the step;
- * the result does not depend on the physical page order.
+ * Work is split along the context, so a few very long resumed trajectories do not
+ * serialise the step: for bf16 / D = 128 / page 16 the (kv head, page) slabs of the
+ * whole pool form one stream that is cut into equal shares, one per wavefront, and
+ * the pieces of a sequence are combined in share order; other shapes split every
+ * context into 512-token chunks, combined in chunk order.  Either way the partition
+ * depends on ctx_len only: results are bitwise reproducible and do not depend on the
+ * physical page order.
  *
  *   q           [C, Hq, D]                      dtype
  *   k_cache     [num_pages, Hkv, page_size, D]  dtype; RoPE already applied
@@ -115,7 +120,10 @@ void copris_set_launch_hook(copris_launch_hook_fn hook, void* user);
  * Slots of a last page at or past ctx_len, and pages the block table does not
  * reference, are never allowed to influence the result (they may hold NaN).
  * ctx_len[i] == 0 gives out = 0, lse = -inf.
- * Supported: D in {64, 128}; page_size 16; Hq/Hkv <= 16; C*Hkv < 2^20.
+ * Every block_table entry that is used must lie in [0, num_pages) (not checked: that
+ * would need a device round trip).
+ * Supported: D in {64, 128}; page_size a divisor of 512; Hq/Hkv <= 16; C*Hkv < 2^20;
+ * C * ceil(max_pages*page_size / 512) * Hkv < 2^31.
  * ------------------------------------------------------------------------ */
 size_t copris_decode_attn_workspace_bytes(int C, int Hq, int Hkv, int D,
                                           int page_size, int max_pages);

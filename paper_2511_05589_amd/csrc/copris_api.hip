@@ -19,6 +19,10 @@ bool attn_shape_ok(int C, int Hq, int Hkv, int D, int page_size, int max_pages) 
   if (Hq % Hkv != 0) return false;
   if (static_cast<int64_t>(max_pages) * page_size > (1ll << 30)) return false;
   if (static_cast<int64_t>(C) * Hkv >= (1ll << 20)) return false;
+  // the generic path indexes (sequence, 512-token chunk, kv head) items with 32 bits
+  const int64_t chunks = (static_cast<int64_t>(max_pages) * page_size + copris::kAttnChunkTokens - 1) /
+                         copris::kAttnChunkTokens;
+  if (static_cast<int64_t>(C) * chunks * Hkv >= (1ll << 31)) return false;
   return true;
 }
 

@@ -5,15 +5,19 @@
 // and cut into equal contiguous shares, one per persistent wavefront ("stream-K"): the
 // split is balanced to one page whatever the length distribution, a 32k-token resumed
 // trajectory is simply spread over many wavefronts, and nothing is scheduled at run time.
-//   scan kernel    ctx_len -> page prefix sums, slots per wavefront, and each wavefront's
-//                  start cursor (sequence, kv head, page) in the slot stream
-//   split kernel   one wavefront per share: walks its slots with a wave-uniform cursor
-//                  (physical pages from the block table, one slot ahead) and a
-//                  three-page-deep register prefetch; whenever the (sequence, kv head)
-//                  changes it writes the online-softmax partial (running max, weight sum,
-//                  weighted value sum) of the g query heads that share the kv head
-//   merge kernel   per (sequence, kv head): log-sum-exp combination of the partials in
-//                  share order, normalisation, store
+//   split kernel   one wavefront per share.  It first derives its own start cursor
+//                  (sequence, kv head, page) from ctx_len with one wave-level prefix sum
+//                  (no separate pass over ctx_len, no extra launch), then walks its slots
+//                  with a wave-uniform cursor (physical pages from the block table, one
+//                  slot ahead) and a three-page-deep register prefetch.  Whenever the
+//                  (sequence, kv head) segment changes: a segment that lies wholly inside
+//                  the share is normalised and stored to `out` right there; one that a
+//                  share boundary cuts leaves its online-softmax partial (running max,
+//                  weight sum, weighted value sum of the g query heads of the kv head)
+//   merge kernel   per (sequence, kv head) that a boundary cuts: log-sum-exp combination
+//                  of the partials in share order, normalisation, store; it also writes
+//                  the zeros of empty sequences
+// (For more than 4096 sequences a one-workgroup scan kernel computes the cursors first.)
 // The partition depends on ctx_len only, the merge order is fixed: results are bitwise
 // reproducible and do not depend on the physical page order.
 //
@@ -358,21 +362,121 @@ __device__ __forceinline__ int swz_v(int row, int c) { return row * 16 + (c ^ ((
 // s_waitcnt vmcnt(0) with the other counters left alone (gfx9 encoding)
 #define COPRIS_WAIT_VM0() __builtin_amdgcn_s_waitcnt(0x0F70)
 
-template <int NS>
+// Pages of sequence i as the kernels count them.
+__device__ __forceinline__ int attn_pages_of(const int32_t* __restrict__ ctx_len, int i, int max_tokens) {
+  const int n = min(max(ctx_len[i], 0), max_tokens);
+  return (n + kP - 1) / kP;
+}
+
+// One wavefront: total pages of the pool and the start cursor of slot `w * share` of the
+// slot stream, from ctx_len alone.  Lane l owns the sequences [l*chunk, (l+1)*chunk); an
+// inclusive prefix sum over the lanes gives the pages before each lane's range; the one
+// lane whose range holds the slot walks its (at most `chunk`) sequences.  Returns the
+// cursor in every lane ({-1,..}: no slot for this wavefront) and total / share by reference.
+__device__ __forceinline__ int4 attn_derive_cursor(const int32_t* __restrict__ ctx_len, int C,
+                                                   int max_tokens, int Hkv, int w, int& total,
+                                                   int& share) {
+  const int lane = threadIdx.x & (kWave - 1);
+  const int chunk = (C + kWave - 1) / kWave;
+  const int i0 = min(lane * chunk, C), i1 = min(i0 + chunk, C);
+  // up to 8 sequences per lane (C <= 512) stay in registers, so that the walk below costs
+  // no second round trip to memory
+  constexpr int kReg = 8;
+  int reg[kReg];
+  int mine = 0;
+  if (chunk <= kReg) {
+#pragma unroll
+    for (int j = 0; j < kReg; ++j) {
+      reg[j] = i0 + j < i1 ? attn_pages_of(ctx_len, i0 + j, max_tokens) : 0;
+      mine += reg[j];
+    }
+  } else {
+    for (int i = i0; i < i1; ++i) mine += attn_pages_of(ctx_len, i, max_tokens);
+  }
+  int incl = mine;
+#pragma unroll
+  for (int o = 1; o < kWave; o <<= 1) {
+    const int up = __shfl_up(incl, o, kWave);
+    if (lane >= o) incl += up;
+  }
+  const int pages = __shfl(incl, kWave - 1, kWave);
+  total = pages * Hkv;
+  share = total > 0 ? (total + kAttnWaves - 1) / kAttnWaves : 1;
+  const int64_t slot = static_cast<int64_t>(w) * share;
+  int4 st = make_int4(-1, 0, 0, 0);
+  if (slot >= total) return st;
+  const int64_t before = static_cast<int64_t>(incl - mine) * Hkv;     // slots before this lane's range
+  const bool holds = before <= slot && slot < before + static_cast<int64_t>(mine) * Hkv;
+  const uint64_t ball = __builtin_amdgcn_ballot_w64(holds);            // exactly one lane
+  const int owner = __builtin_ctzll(ball);
+  if (holds) {
+    int64_t pg0 = incl - mine;
+    if (chunk <= kReg) {
+      bool found = false;
+#pragma unroll
+      for (int j = 0; j < kReg; ++j) {
+        const int npg = reg[j];
+        if (!found && slot < (pg0 + npg) * Hkv) {
+          const int r = static_cast<int>(slot - pg0 * Hkv);
+          st = make_int4(i0 + j, r / npg, r % npg, npg);
+          found = true;
+        }
+        pg0 += found ? 0 : npg;
+      }
+    } else {
+      for (int i = i0; i < i1; ++i) {
+        const int npg = attn_pages_of(ctx_len, i, max_tokens);
+        if (slot < (pg0 + npg) * Hkv) {
+          const int r = static_cast<int>(slot - pg0 * Hkv);
+          st = make_int4(i, r / npg, r % npg, npg);
+          break;
+        }
+        pg0 += npg;
+      }
+    }
+  }
+  st.x = __shfl(st.x, owner, kWave);
+  st.y = __shfl(st.y, owner, kWave);
+  st.z = __shfl(st.z, owner, kWave);
+  st.w = __shfl(st.w, owner, kWave);
+  return st;
+}
+
+// entry word of a slot: tokens of the page inside the context - 1 (4 bits), first / last
+// page of its (sequence, kv head) segment (1 + 1), kv head (8), sequence (17)
+constexpr int kCodeFirst = 1 << 4, kCodeLast = 1 << 5, kCodeKvhShift = 6, kCodeSeqShift = 14;
+constexpr int kAttnMaxSeqTuned = 1 << 17;
+constexpr int kAttnMaxSeqInKernelCursor = 4096;
+
+template <int NS, bool PRESCAN>
 __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2))) void attn_split_flat_kernel(
     const uint16_t* __restrict__ q, const u32x4* __restrict__ k_cache,
     const u32x4* __restrict__ v_cache, const int32_t* __restrict__ block_table,
     const int32_t* __restrict__ ctx_len, const int32_t* __restrict__ hdr,
-    const int4* __restrict__ start, float2* __restrict__ ws_ml, float* __restrict__ ws_acc, int C,
-    int Hq, int Hkv, int g, int max_pages, int max_tokens, float scale_log2e) {
+    const int4* __restrict__ start, float2* __restrict__ ws_ml, float* __restrict__ ws_acc,
+    uint16_t* __restrict__ out, float* __restrict__ lse, int C, int Hq, int Hkv, int g,
+    int max_pages, int max_tokens, float scale_log2e) {
   __shared__ u32x4 lds_k[kPageGranules];
   __shared__ u32x4 lds_v[kPageGranules];
   const int lane = threadIdx.x;
   const int head = lane & 15;     // N index of both products: the query head of the group
   const int b = lane >> 4;        // k-group of the MFMA operand layouts
-  const int total = hdr[0], share = hdr[1];
   const int wv = blockIdx.x;
-  const int4 st = start[wv];
+  int total, share;
+  int4 st;
+  if (PRESCAN) {
+    total = hdr[0];
+    share = hdr[1];
+    st = start[wv];
+  } else {
+    st = attn_derive_cursor(ctx_len, C, max_tokens, Hkv, wv, total, share);
+    st.x = __builtin_amdgcn_readfirstlane(st.x);
+    st.y = __builtin_amdgcn_readfirstlane(st.y);
+    st.z = __builtin_amdgcn_readfirstlane(st.z);
+    st.w = __builtin_amdgcn_readfirstlane(st.w);
+    total = __builtin_amdgcn_readfirstlane(total);
+    share = __builtin_amdgcn_readfirstlane(share);
+  }
   if (st.x < 0) return;
   const int64_t first = static_cast<int64_t>(wv) * share;
   const int n = static_cast<int>(min(static_cast<int64_t>(share), total - first));   // slots of this wavefront
@@ -385,7 +489,8 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2))) void
   int f_page = block_table[static_cast<size_t>(f_seq) * max_pages + f_p];
   auto next_entry = [&](int& page, int& code) __attribute__((always_inline)) {
     page = f_page;
-    code = (min(kP, f_ctx - f_p * kP) - 1) | (f_kvh << 4) | (f_seq << 12);
+    code = (min(kP, f_ctx - f_p * kP) - 1) | (f_p == 0 ? kCodeFirst : 0) |
+           (f_p + 1 == f_npg ? kCodeLast : 0) | (f_kvh << kCodeKvhShift) | (f_seq << kCodeSeqShift);
     if (++f_p == f_npg) {
       f_p = 0;
       if (++f_kvh == Hkv) {   // on to the next sequence that has a context
@@ -406,10 +511,32 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2))) void
   float m_run = -INFINITY, l_run = 0.0f;
   f32x4 o[8];
 
-  auto flush = [&]() __attribute__((always_inline)) {   // partial of (this wavefront, cur_seg)
+  bool seg_whole = false;   // the segment began with its first page inside this share
+  bool seg_ends = false;    // the slot just processed was the segment's last page
+  auto flush = [&]() __attribute__((always_inline)) {   // result of (this wavefront, cur_seg)
     float l_all = l_run;
     l_all += __shfl_xor(l_all, 16, kWave);
     l_all += __shfl_xor(l_all, 32, kWave);
+    if (seg_whole && seg_ends) {
+      // no other wavefront saw this segment: normalise and store (lane (head, b) owns
+      // d = 16dt + 4b + r); same arithmetic as the merge of a single partial
+      if (head < g) {
+        const int seq = cur_seg / Hkv, kvh = cur_seg - seq * Hkv;
+        const size_t oh = static_cast<size_t>(seq) * Hq + kvh * g + head;
+        uint16_t* dst = out + oh * kD + 4 * b;
+#pragma unroll
+        for (int dt = 0; dt < 8; ++dt) {
+          ushort4 r;
+          r.x = f32_to_bf16(o[dt][0] / l_all);
+          r.y = f32_to_bf16(o[dt][1] / l_all);
+          r.z = f32_to_bf16(o[dt][2] / l_all);
+          r.w = f32_to_bf16(o[dt][3] / l_all);
+          *reinterpret_cast<ushort4*>(dst + 16 * dt) = r;
+        }
+        if (lse != nullptr && b == 0) lse[oh] = (m_run + __builtin_amdgcn_logf(l_all)) * kLn2;
+      }
+      return;
+    }
     if (head < g) {
       const size_t slot = (static_cast<size_t>(wv) + cur_seg) * g + head;
       float* dst = ws_acc + slot * kD + 4 * b;    // lane (head, b) owns d = 16dt + 4b + r
@@ -446,11 +573,13 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2))) void
   auto do_slot = [&](PageRegs& r, int& code, const int i, auto steady) __attribute__((always_inline)) {
     constexpr bool kSteady = decltype(steady)::value;
     const int valid = (code & 15) + 1;           // tokens of this page inside the context
-    const int kvh = (code >> 4) & 255, seq = code >> 12;
+    const int kvh = (code >> kCodeKvhShift) & 255, seq = code >> kCodeSeqShift;
     if (seq * Hkv + kvh != cur_seg) {
       if (cur_seg >= 0) flush();
       begin_segment(seq, kvh);
+      seg_whole = (code & kCodeFirst) != 0;     // ... so far: it starts inside this share
     }
+    seg_ends = (code & kCodeLast) != 0;
     // granule (j*64+lane) = token row 4j+b, column granule `head`
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
@@ -460,7 +589,7 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2))) void
     if (kSteady || i + NS < n) {
       int page;
       next_entry(page, code);
-      load_page(r, k_cache, v_cache, page, Hkv, (code >> 4) & 255, lane);
+      load_page(r, k_cache, v_cache, page, Hkv, (code >> kCodeKvhShift) & 255, lane);
     }
     __syncthreads();
 
@@ -521,18 +650,18 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2))) void
   {
     int page;
     next_entry(page, c0);
-    load_page(st0, k_cache, v_cache, page, Hkv, (c0 >> 4) & 255, lane);
+    load_page(st0, k_cache, v_cache, page, Hkv, (c0 >> kCodeKvhShift) & 255, lane);
   }
   if (n >= 2 * NS) {
     {
       int page;
       next_entry(page, c1);
-      load_page(st1, k_cache, v_cache, page, Hkv, (c1 >> 4) & 255, lane);
+      load_page(st1, k_cache, v_cache, page, Hkv, (c1 >> kCodeKvhShift) & 255, lane);
     }
     {
       int page;
       next_entry(page, c2);
-      load_page(st2, k_cache, v_cache, page, Hkv, (c2 >> 4) & 255, lane);
+      load_page(st2, k_cache, v_cache, page, Hkv, (c2 >> kCodeKvhShift) & 255, lane);
     }
     do {   // steady state: every refill exists
       do_slot(st0, c0, i, std::true_type{});
@@ -544,12 +673,12 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2))) void
     if (1 < n) {
       int page;
       next_entry(page, c1);
-      load_page(st1, k_cache, v_cache, page, Hkv, (c1 >> 4) & 255, lane);
+      load_page(st1, k_cache, v_cache, page, Hkv, (c1 >> kCodeKvhShift) & 255, lane);
     }
     if (2 < n) {
       int page;
       next_entry(page, c2);
-      load_page(st2, k_cache, v_cache, page, Hkv, (c2 >> 4) & 255, lane);
+      load_page(st2, k_cache, v_cache, page, Hkv, (c2 >> kCodeKvhShift) & 255, lane);
     }
   }
   for (; i < n; i += NS) {   // the last 3..5 slots of the share (or a short share)
@@ -614,39 +743,102 @@ __global__ void attn_merge_kernel(const int32_t* __restrict__ seq_off,
 
 // Merge for the flat slot stream: segment (seq, kv head) occupies slots [a, a+npg) and was
 // touched by the wavefronts a/share .. (a+npg-1)/share; the partial of (wavefront w,
-// segment s) sits at index w + s.
-__global__ __launch_bounds__(256) void attn_merge_flat_kernel(const int32_t* __restrict__ hdr,
+// segment s) sits at index w + s.  A segment inside one share was stored by its wavefront
+// already; an empty sequence gets its zeros here.
+template <bool PRESCAN>
+__global__ __launch_bounds__(256) void attn_merge_flat_kernel(const int32_t* __restrict__ ctx_len,
+                                                              const int32_t* __restrict__ hdr,
                                                               const int32_t* __restrict__ seq_pg,
                                                               const float2* __restrict__ ws_ml,
                                                               const float* __restrict__ ws_acc,
                                                               uint16_t* __restrict__ out,
-                                                              float* __restrict__ lse, int Hq, int Hkv,
-                                                              int g) {
+                                                              float* __restrict__ lse, int C, int Hq,
+                                                              int Hkv, int g, int max_tokens) {
   // one workgroup per (sequence, kv head); a thread owns four head_dim indices of one head
+  __shared__ int s_before[256 / kWave], s_all[256 / kWave];
   const int seq = blockIdx.x, kvh = blockIdx.y;
-  const int share = hdr[1];
-  const int npg = seq_pg[seq + 1] - seq_pg[seq];
-  const int64_t a = static_cast<int64_t>(seq_pg[seq]) * Hkv + static_cast<int64_t>(kvh) * npg;
+  int share, npg, pg0;
+  if (PRESCAN) {
+    share = hdr[1];
+    pg0 = seq_pg[seq];
+    npg = seq_pg[seq + 1] - pg0;
+  } else {
+    // pages before this sequence and in total, from ctx_len (the same counts the split
+    // kernel's wavefronts derived their cursors from)
+    int before = 0, all = 0;
+    for (int i = threadIdx.x; i < C; i += 256) {
+      const int pgs = attn_pages_of(ctx_len, i, max_tokens);
+      all += pgs;
+      before += i < seq ? pgs : 0;
+    }
+    before = wave_sum_i(before);
+    all = wave_sum_i(all);
+    if ((threadIdx.x & (kWave - 1)) == 0) {
+      s_before[threadIdx.x / kWave] = before;
+      s_all[threadIdx.x / kWave] = all;
+    }
+    __syncthreads();
+    pg0 = 0;
+    int pages = 0;
+#pragma unroll
+    for (int w = 0; w < 256 / kWave; ++w) {
+      pg0 += s_before[w];
+      pages += s_all[w];
+    }
+    const int total = pages * Hkv;
+    share = total > 0 ? (total + kAttnWaves - 1) / kAttnWaves : 1;
+    npg = attn_pages_of(ctx_len, seq, max_tokens);
+  }
+  const int64_t a = static_cast<int64_t>(pg0) * Hkv + static_cast<int64_t>(kvh) * npg;
   const int seg = seq * Hkv + kvh;
   const int w0 = npg > 0 ? static_cast<int>(a / share) : 0;
   const int n = npg > 0 ? static_cast<int>((a + npg - 1) / share) - w0 + 1 : 0;
+  if (n == 1) return;   // stored by the one wavefront that saw it
   for (int idx = threadIdx.x; idx < g * (kD / 4); idx += 256) {
     const int h = idx / (kD / 4), d4 = idx - h * (kD / 4);
     const size_t slot0 = (static_cast<size_t>(w0) + seg) * g + h;   // consecutive wavefronts: stride g
     float m_star = -INFINITY;
-    for (int e = 0; e < n; ++e) m_star = fmaxf(m_star, ws_ml[slot0 + static_cast<size_t>(e) * g].x);
     float denom = 0.0f;
     float4 num = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
-    for (int e = 0; e < n; ++e) {
-      const size_t slot = slot0 + static_cast<size_t>(e) * g;
-      const float2 ml = ws_ml[slot];
-      const float4 x = *reinterpret_cast<const float4*>(ws_acc + slot * kD + 4 * d4);
-      const float w = __builtin_amdgcn_exp2f(ml.x - m_star);
-      denom = fmaf(w, ml.y, denom);
-      num.x = fmaf(w, x.x, num.x);
-      num.y = fmaf(w, x.y, num.y);
-      num.z = fmaf(w, x.z, num.z);
-      num.w = fmaf(w, x.w, num.w);
+    constexpr int kFast = 6;
+    if (n <= kFast) {
+      // the usual case: all partials in flight at once (one round trip), then the same
+      // arithmetic in the same order as the loop below
+      float2 ml[kFast];
+      float4 x[kFast];
+#pragma unroll
+      for (int e = 0; e < kFast; ++e) {
+        const size_t slot = slot0 + static_cast<size_t>(e < n ? e : 0) * g;
+        ml[e] = ws_ml[slot];
+        x[e] = *reinterpret_cast<const float4*>(ws_acc + slot * kD + 4 * d4);
+      }
+#pragma unroll
+      for (int e = 0; e < kFast; ++e)
+        if (e < n) m_star = fmaxf(m_star, ml[e].x);
+#pragma unroll
+      for (int e = 0; e < kFast; ++e) {
+        if (e < n) {
+          const float w = __builtin_amdgcn_exp2f(ml[e].x - m_star);
+          denom = fmaf(w, ml[e].y, denom);
+          num.x = fmaf(w, x[e].x, num.x);
+          num.y = fmaf(w, x[e].y, num.y);
+          num.z = fmaf(w, x[e].z, num.z);
+          num.w = fmaf(w, x[e].w, num.w);
+        }
+      }
+    } else {
+      for (int e = 0; e < n; ++e) m_star = fmaxf(m_star, ws_ml[slot0 + static_cast<size_t>(e) * g].x);
+      for (int e = 0; e < n; ++e) {
+        const size_t slot = slot0 + static_cast<size_t>(e) * g;
+        const float2 ml = ws_ml[slot];
+        const float4 x = *reinterpret_cast<const float4*>(ws_acc + slot * kD + 4 * d4);
+        const float w = __builtin_amdgcn_exp2f(ml.x - m_star);
+        denom = fmaf(w, ml.y, denom);
+        num.x = fmaf(w, x.x, num.x);
+        num.y = fmaf(w, x.y, num.y);
+        num.z = fmaf(w, x.z, num.z);
+        num.w = fmaf(w, x.w, num.w);
+      }
     }
     const size_t oh = static_cast<size_t>(seq) * Hq + kvh * g + h;
     ushort4 r = make_ushort4(0, 0, 0, 0);
@@ -681,24 +873,43 @@ int launch_decode_attn(const void* q, const void* k_cache, const void* v_cache,
   const int max_tokens = static_cast<int>(max_tokens64);
   const float scale_log2e = scale * kLog2e;
 
-  // the flat slot stream packs the kv head in 8 bits and the sequence in 19
-  const bool tuned = dtype == 1 && D == kD && page_size == kP && Hkv <= 256 && C < (1 << 19) &&
+  // the flat slot stream packs the kv head in 8 bits and the sequence in 17
+  const bool tuned = dtype == 1 && D == kD && page_size == kP && Hkv <= 256 && C < kAttnMaxSeqTuned &&
                      static_cast<int64_t>(C) * max_pages * Hkv < (1ll << 31);
   if (tuned) {
     int4* start = reinterpret_cast<int4*>(list);   // kAttnWaves start cursors (the list area is larger)
-    COPRIS_PRE("attn_scan_kernel");
-    hipLaunchKernelGGL(attn_scan_kernel, dim3(1), dim3(kListThreads), 0, stream, ctx_len, C,
-                       max_tokens, Hkv, hdr, seq_off, start);
-    COPRIS_POST("attn_scan_kernel");
+    const bool prescan = C > kAttnMaxSeqInKernelCursor;
+    if (prescan) {
+      COPRIS_PRE("attn_scan_kernel");
+      hipLaunchKernelGGL(attn_scan_kernel, dim3(1), dim3(kListThreads), 0, stream, ctx_len, C,
+                         max_tokens, Hkv, hdr, seq_off, start);
+      COPRIS_POST("attn_scan_kernel");
+    }
     COPRIS_PRE("attn_split_flat_kernel");
-    hipLaunchKernelGGL(attn_split_flat_kernel<3>, dim3(kAttnWaves), dim3(64), 0, stream,
-                       static_cast<const uint16_t*>(q), static_cast<const u32x4*>(k_cache),
-                       static_cast<const u32x4*>(v_cache), block_table, ctx_len, hdr, start, ws_ml,
-                       ws_acc, C, Hq, Hkv, g, max_pages, max_tokens, scale_log2e);
+    if (prescan) {
+      hipLaunchKernelGGL((attn_split_flat_kernel<3, true>), dim3(kAttnWaves), dim3(64), 0, stream,
+                         static_cast<const uint16_t*>(q), static_cast<const u32x4*>(k_cache),
+                         static_cast<const u32x4*>(v_cache), block_table, ctx_len, hdr, start, ws_ml,
+                         ws_acc, static_cast<uint16_t*>(out), lse, C, Hq, Hkv, g, max_pages, max_tokens,
+                         scale_log2e);
+    } else {
+      hipLaunchKernelGGL((attn_split_flat_kernel<3, false>), dim3(kAttnWaves), dim3(64), 0, stream,
+                         static_cast<const uint16_t*>(q), static_cast<const u32x4*>(k_cache),
+                         static_cast<const u32x4*>(v_cache), block_table, ctx_len, hdr, start, ws_ml,
+                         ws_acc, static_cast<uint16_t*>(out), lse, C, Hq, Hkv, g, max_pages, max_tokens,
+                         scale_log2e);
+    }
     COPRIS_POST("attn_split_flat_kernel");
     COPRIS_PRE("attn_merge_flat_kernel");
-    hipLaunchKernelGGL(attn_merge_flat_kernel, dim3(C, Hkv), dim3(256), 0, stream, hdr, seq_off,
-                       ws_ml, ws_acc, static_cast<uint16_t*>(out), lse, Hq, Hkv, g);
+    if (prescan) {
+      hipLaunchKernelGGL(attn_merge_flat_kernel<true>, dim3(C, Hkv), dim3(256), 0, stream, ctx_len, hdr,
+                         seq_off, ws_ml, ws_acc, static_cast<uint16_t*>(out), lse, C, Hq, Hkv, g,
+                         max_tokens);
+    } else {
+      hipLaunchKernelGGL(attn_merge_flat_kernel<false>, dim3(C, Hkv), dim3(256), 0, stream, ctx_len, hdr,
+                         seq_off, ws_ml, ws_acc, static_cast<uint16_t*>(out), lse, C, Hq, Hkv, g,
+                         max_tokens);
+    }
     COPRIS_POST("attn_merge_flat_kernel");
     return 0;
   }

@@ -94,6 +94,16 @@ def test_single_head_group_and_many_short_sequences(R):
     _run_case(R, case, W.BF16, "g=1 short")
 
 
+def test_thousands_of_sequences(R):
+    # more sequences than a wavefront derives its own cursor for: a scan kernel prepares them;
+    # with contexts of a page or two nearly every segment lies inside one share, and some shares
+    # hold dozens of whole segments
+    rng = np.random.default_rng(4)
+    ctx = rng.integers(0, 34, size=4500).tolist()
+    case = W.make_small_decode_case(23, len(ctx), 6, 2, 128, W.BF16, 16, ctx)
+    _run_case(R, case, W.BF16, "4500 sequences")
+
+
 def test_large_scores_do_not_overflow(R):
     case = W.make_small_decode_case(8, 2, 7, 1, 128, W.BF16, 16, [600, 31], poison=True)
     q = W.to_f32(case["q"], W.BF16) * 40.0           # scores of magnitude ~ 10^2..10^3 * scale
