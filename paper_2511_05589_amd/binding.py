@@ -12,7 +12,8 @@ from ctypes import c_char_p, c_float, c_int, c_int64, c_size_t, c_uint64, c_void
 from typing import Optional
 
 _PKG_DIR = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_PKG_DIR, "libcopris.so")
+# COPRIS_LIB selects another build of the library (e.g. one with host sanitizers)
+LIB_PATH = os.environ.get("COPRIS_LIB") or os.path.join(_PKG_DIR, "libcopris.so")
 
 COPRIS_OK = 0
 COPRIS_EINVAL = -1

@@ -61,5 +61,21 @@ def build(verbose: bool = False, lib_path: str = LIB_PATH, extra_flags=()) -> st
     return lib_path
 
 
+HOST_SANITIZE = ["-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined",
+                 "-Xarch_host", "-fno-omit-frame-pointer", "-g"]
+
+
 if __name__ == "__main__":
-    print(build(verbose=True))
+    import argparse
+    ap = argparse.ArgumentParser(description=__doc__)
+    ap.add_argument("--out", default=LIB_PATH, help="path of the shared library to write")
+    ap.add_argument("--host-sanitize", action="store_true",
+                    help="instrument the HOST code (argument checks, launchers, rollout manager) with "
+                         "AddressSanitizer + UBSan; device code is built as usual.  Load the result with "
+                         "COPRIS_LIB=<out> and the sanitizer runtime preloaded")
+    ap.add_argument("--define", action="append", default=[], metavar="NAME",
+                    help="define a preprocessor symbol (the timing probes documented in csrc/lmhead.hip); "
+                         "use with --out: such a build computes wrong results by design")
+    a = ap.parse_args()
+    flags = (HOST_SANITIZE if a.host_sanitize else []) + ["-D" + d for d in a.define]
+    print(build(verbose=True, lib_path=os.path.abspath(a.out), extra_flags=flags))

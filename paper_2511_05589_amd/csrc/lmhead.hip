@@ -328,6 +328,22 @@ __device__ __forceinline__ u32x4 lds_read128(uint32_t addr) {
 // (Waits on these reads are inline "s_waitcnt lgkmcnt(N)" statements that tie the operands
 // which must have arrived, so that no use can be scheduled above the wait.)
 
+// Timing probes (never defined in the product build; `python -m paper_2511_05589_amd.build
+// --define NAME --out other.so` builds one, bench.py --lib times it; the results of such a
+// build are wrong by design, every access stays in bounds and every loop ends):
+//   COPRIS_LM_PROBE_NO_MFMA      the matrix products become one scalar multiply-add each
+//   COPRIS_LM_PROBE_NO_EPILOGUE  no log-sum-exp / sampling after a tile
+//   COPRIS_LM_PROBE_NO_W_LOADS   the W stream is not requested (operands are whatever LDS holds)
+//   COPRIS_LM_PROBE_NO_H_LOADS   the hidden stream is not requested
+//   COPRIS_LM_PROBE_W_FROM_L2    every workgroup re-reads the first two vocabulary tiles
+// They separate what bounds the kernel: the memory pipeline alone, the products alone, the
+// lead of the W stream.
+#if defined(COPRIS_LM_PROBE_NO_MFMA)
+#define COPRIS_LM_MFMA(fa, fb, c) ((c)[0] += static_cast<float>((fa)[0]) * static_cast<float>((fb)[0]), (c))
+#else
+#define COPRIS_LM_MFMA(fa, fb, c) __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa, fb, c, 0, 0, 0)
+#endif
+
 template <bool GIVEN>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void lmhead_mfma_kernel(
     const uint16_t* __restrict__ hidden, const uint16_t* __restrict__ weight,
@@ -372,9 +388,17 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   auto w_load = [&](int j) __attribute__((always_inline)) {
     char* dst = smem + w_ring * kSlab + (4 * wave + j) * 1024;
     const uint32_t koff = static_cast<uint32_t>(w_kd) * (kMfBK * 2) + ld_g;
+#if defined(COPRIS_LM_PROBE_W_FROM_L2)
+    const int v = min((w_tile & 1) * kMfBM + ld_row + 8 * j, V - 1);
+#else
     const int v = min(w_tile * kMfBM + ld_row + 8 * j, V - 1);
+#endif
+#if !defined(COPRIS_LM_PROBE_NO_W_LOADS)
     __builtin_amdgcn_global_load_lds(wbase + (static_cast<uint32_t>(v) * pitch + (koff ^ ((j & 1) * 64))), dst,
                                      16, 0, 0);
+#else
+    (void)v; (void)koff; (void)dst;
+#endif
   };
   auto w_advance = [&]() __attribute__((always_inline)) {
     w_ring = w_ring + 1 == kNW ? 0 : w_ring + 1;
@@ -387,8 +411,12 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     char* dst = smem + kHRing + h_ring * kSlab + (4 * wave + j) * 1024;
     const uint32_t koff = static_cast<uint32_t>(h_kd) * (kMfBK * 2) + ld_g;
     const int c = min(c0 + 128 * (h_n & 1) + ld_row + 8 * j, C - 1);
+#if !defined(COPRIS_LM_PROBE_NO_H_LOADS)
     __builtin_amdgcn_global_load_lds(hbase + (static_cast<uint32_t>(c) * pitch + (koff ^ ((j & 1) * 64))), dst,
                                      16, 0, 0);
+#else
+    (void)c; (void)koff; (void)dst;
+#endif
   };
   auto h_advance = [&]() __attribute__((always_inline)) {
     h_ring = h_ring + 1 == kNH ? 0 : h_ring + 1;
@@ -496,7 +524,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
             const int k16 = 2 * grp + (m >> 2), it = (m >> 1) & 1;
             const bf16x8 fa = __builtin_bit_cast(bf16x8, a[k16][it]);
             const bf16x8 fb = __builtin_bit_cast(bf16x8, b[k16][m & 1]);
-            acc[half][it][m & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa, fb, acc[half][it][m & 1], 0, 0, 0);
+            acc[half][it][m & 1] = COPRIS_LM_MFMA(fa, fb, acc[half][it][m & 1]);
             // The twelve loads a wave issues per slab go out one at a time between the
             // products (three per group of eight).  Issued in a bunch they keep every wave
             // of the CU at the issue stage while the address unit works through them, and the
@@ -530,6 +558,13 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     auto epilogue = [&](auto ic) __attribute__((always_inline)) {
       constexpr int i = decltype(ic)::value;       // state index = 2*half + nt
       const int c = c0 + 128 * (i >> 1) + 64 * wq + 32 * (i & 1) + l32;
+#if defined(COPRIS_LM_PROBE_NO_EPILOGUE)
+      if (c < C) {   // keep the accumulators alive, nothing else
+        st[i].s += acc[i >> 1][0][i & 1][0] + acc[i >> 1][1][i & 1][15];
+        st[i].m = 0.0f;
+        st[i].idx = v0;
+      } else
+#endif
       if (c < C && GIVEN) {
         lm_given_block(acc[i >> 1][0][i & 1], st[i], v0 + 64 * wm + 4 * kb, V, tail, inv_temperature,
                        static_cast<int>(step_c[i]));
