@@ -14,6 +14,18 @@ namespace copris {
 
 constexpr int kIsThreads = 1024;
 
+// Every byte of the batch is touched once: non-temporal loads and stores keep the streams out
+// of the L2.  (The builtins take native vector types.)
+typedef float is_f32x4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ float4 load_stream4(const float* p) {
+  const is_f32x4 v = __builtin_nontemporal_load(reinterpret_cast<const is_f32x4*>(p));
+  return make_float4(v[0], v[1], v[2], v[3]);
+}
+__device__ __forceinline__ void store_stream4(float* p, const float4& x) {
+  const is_f32x4 v = {x.x, x.y, x.z, x.w};
+  __builtin_nontemporal_store(v, reinterpret_cast<is_f32x4*>(p));
+}
+
 // Per-token operations.  Both produce two fp32 outputs per token and a per-sequence
 // accumulator; a token that is not counted writes 0 to both (select, never multiply, so
 // that NaNs at masked positions do not leak).
@@ -75,12 +87,12 @@ __device__ __forceinline__ typename Op::Acc stream_sequence(
   for (int64_t gj = gbase + 4 * static_cast<int64_t>(threadIdx.x); gj < j1;
        gj += 4 * static_cast<int64_t>(kIsThreads)) {
     if (gj >= j0 && gj + 4 <= j1) {
-      const float4 c = *reinterpret_cast<const float4*>(logp_cur + gj);
+      const float4 c = load_stream4(logp_cur + gj);
       float4 o;
       if (gj + 4 <= jsplit) {
-        o = *reinterpret_cast<const float4*>(logp_buf + gj);
+        o = load_stream4(logp_buf + gj);
       } else if (gj >= jsplit) {
-        o = *reinterpret_cast<const float4*>(logp_roll + gj);
+        o = load_stream4(logp_roll + gj);
       } else {  // the one group that straddles the stage boundary
         o.x = gj + 0 < jsplit ? logp_buf[gj + 0] : logp_roll[gj + 0];
         o.y = gj + 1 < jsplit ? logp_buf[gj + 1] : logp_roll[gj + 1];
@@ -88,14 +100,14 @@ __device__ __forceinline__ typename Op::Acc stream_sequence(
         o.w = gj + 3 < jsplit ? logp_buf[gj + 3] : logp_roll[gj + 3];
       }
       uint32_t m4 = 0x01010101u;
-      if (HAS_MASK) m4 = *reinterpret_cast<const uint32_t*>(mask + gj);
+      if (HAS_MASK) m4 = __builtin_nontemporal_load(reinterpret_cast<const uint32_t*>(mask + gj));
       float4 r, rc;
       op.token(c.x, o.x, (m4 & 0x000000ffu) != 0, r.x, rc.x, acc);
       op.token(c.y, o.y, (m4 & 0x0000ff00u) != 0, r.y, rc.y, acc);
       op.token(c.z, o.z, (m4 & 0x00ff0000u) != 0, r.z, rc.z, acc);
       op.token(c.w, o.w, (m4 & 0xff000000u) != 0, r.w, rc.w, acc);
-      *reinterpret_cast<float4*>(out0 + gj) = r;
-      *reinterpret_cast<float4*>(out1 + gj) = rc;
+      store_stream4(out0 + gj, r);
+      store_stream4(out1 + gj, rc);
     } else {  // ragged head or tail of the sequence
 #pragma unroll
       for (int e = 0; e < 4; ++e) {

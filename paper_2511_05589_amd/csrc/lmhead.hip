@@ -313,6 +313,7 @@ __device__ __forceinline__ void lm_given_block(const f32x16& acc, LmLaneState& s
 // cannot count LDS-direct loads per buffer (it
 // would drain them all before any LDS read), so the operand reads are inline ds_read_b128
 // and every wait is explicit.  80 KB of LDS per workgroup: two workgroups fill a CU's 160 KB.
+constexpr int kLmStreamOnce = 2;                    // cache policy of the W loads: non-temporal (every byte is read once)
 constexpr int kNW = 2;                              // W ring slabs
 constexpr int kNH = 3;                              // hidden ring units
 constexpr int kSlab = 128 * kMfBK * 2;              // 16 KB: a W slab or a hidden unit
@@ -395,7 +396,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 #endif
 #if !defined(COPRIS_LM_PROBE_NO_W_LOADS)
     __builtin_amdgcn_global_load_lds(wbase + (static_cast<uint32_t>(v) * pitch + (koff ^ ((j & 1) * 64))), dst,
-                                     16, 0, 0);
+                                     16, 0, kLmStreamOnce);
 #else
     (void)v; (void)koff; (void)dst;
 #endif
