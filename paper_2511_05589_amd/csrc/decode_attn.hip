@@ -595,6 +595,17 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2))) void
       load_page(r, k_cache, v_cache, page, Hkv, (code >> kCodeKvhShift) & 255, lane);
     }
     __syncthreads();
+#if defined(COPRIS_ATTN_PROBE_NO_COMPUTE)
+    // timing probe: the page is fetched and parked, nothing is computed from it
+    {
+      const u32x4 kk0 = lds_k[lane];
+      const u32x4 vv0 = lds_v[lane];
+      l_run += __uint_as_float((kk0[0] ^ vv0[1]) & 0x3fffffffu);
+      (void)valid;
+      __syncthreads();
+      return;
+    }
+#endif
 
     // S^T[token][head]: A = K rows (token = lane&15), B = Q^T
     f32x4 sc = {0.0f, 0.0f, 0.0f, 0.0f};

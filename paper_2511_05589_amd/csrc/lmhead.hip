@@ -301,18 +301,17 @@ __device__ __forceinline__ void lm_given_block(const f32x16& acc, LmLaneState& s
 // Both operands reach LDS through LDS-direct loads (global_load_lds_dwordx4: each
 // lane's 16 bytes land at base + 16*lane, no registers in between), so the data in
 // flight lives in LDS rings:
-//   W       [128 rows][64 k] slabs of 16 KB, ring of two, issued one slab ahead;
+//   W       [128 rows][64 k] slabs of 16 KB, ring of two, issued a slab and a half ahead (a
+//           slab's slot is given away as soon as every wave has its operands in registers);
 //   hidden  [128 rows][64 k] units of 16 KB - the two batch halves of a slab are
 //           consumed one after the other against the same W slab - ring of three,
 //           issued two units (one slab) ahead.
 // Every wave issues a quarter of each slab and unit, one load at a time between the matrix
 // products.  The outstanding-load counter of a wave retires in order, so the issue order is
 // chosen such that what a wait needs is always older than what may stay in flight: per slab
-// d W(d+1) first (it comes from HBM and needs the longest lead), then hidden(2d+2) - the
-// last two of its four loads after the middle barrier - then hidden(2d+3).  The compiler
-// cannot count LDS-direct loads per buffer (it
-// would drain them all before any LDS read), so the operand reads are inline ds_read_b128
-// and every wait is explicit.  80 KB of LDS per workgroup: two workgroups fill a CU's 160 KB.
+// d hidden (d+1, half 0), then W(d+2), and after the middle barrier hidden (d+1, half 1).  The
+// compiler cannot count LDS-direct loads per buffer (it would drain them all before any LDS
+// read), so the operand reads are inline ds_read_b128 and every wait is explicit.  80 KB of LDS per workgroup: two workgroups fill a CU's 160 KB.
 constexpr int kLmStreamOnce = 2;                    // cache policy of the W loads: non-temporal (every byte is read once)
 constexpr int kNW = 2;                              // W ring slabs
 constexpr int kNH = 3;                              // hidden ring units
@@ -455,18 +454,21 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     }
   }
 
-  // prologue.  A wave's loads complete in issue order, and that order is, per slab d:
-  // W(d+1) and half of hidden(2d+2) before the middle barrier, the rest of hidden(2d+2) and
-  // hidden(2d+3) after it.  So at the top the wave may leave its newest four loads
-  // (hidden(2d+1)) in flight and knows W(d) and hidden(2d) have landed; at mid-slab it may
-  // leave the six issued since the top and knows hidden(2d+1) has.
+  // prologue = the loads of "slabs -2 and -1".  A wave's loads complete in issue order, and
+  // that order is, per slab d: hidden (d+1, half 0), W(d+2) | hidden (d+1, half 1).  So at the
+  // top of slab d the wave may leave its newest eight loads (W(d+1), hidden (d, 1)) in flight
+  // and knows hidden (d, 0) has landed; at mid-slab it may leave the eight issued since the
+  // top and knows W(d+1) and hidden (d, 1) have.
   if (total > 0) {
+    issue_w();
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // W(0): the first slab reads it before any barrier of the loop
     issue_h();
     issue_w();
     issue_h();
   }
+  asm volatile("s_barrier" ::: "memory");
 
-  int d_idx = 0, ring = 0, hring = 0;          // W slab being consumed (flat index), W / hidden ring slots
+  int ring = 0, hring = 0;                     // W / hidden ring slots being consumed
   for (int tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
     const int v0 = tile * kMfBM;
     f32x16 acc[2][2][2];                       // [batch half][it][nt]
@@ -475,25 +477,32 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i >> 2][(i >> 1) & 1][i & 1][r] = 0.0f;
 
-    for (int kd = 0; kd < nkd; ++kd, ++d_idx) {
-      // ---- top: W slab d_idx and hidden unit (d_idx, half 0) have landed ----
-      asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
-      asm volatile("s_barrier" ::: "memory");   // ... for every wave; all are done with slab d_idx-1
+    for (int kd = 0; kd < nkd; ++kd) {
+      // The W operands of the slab go to registers BEFORE the top barrier (the slab has been
+      // in LDS, for every wave, since the middle barrier of the slab before), so that barrier
+      // also says "every wave holds its operands": the slot of W(d) is free from there on and
+      // W(d+2) is requested right away - a slab is on its way for a slab and a half although
+      // the ring holds only two.
       const uint32_t wb = lds0 + ring * kSlab;
-      ring = ring + 1 == kNW ? 0 : ring + 1;
+      ring ^= 1;
       u32x4 a[4][2];
 #pragma unroll
       for (int k16 = 0; k16 < 4; ++k16) {
         a[k16][0] = lds_read128<0>(wb + a_off[k16]);
         a[k16][1] = lds_read128<4096>(wb + a_off[k16]);
       }
+      asm volatile("s_waitcnt lgkmcnt(0)"
+                   : "+v"(a[0][0]), "+v"(a[0][1]), "+v"(a[1][0]), "+v"(a[1][1]), "+v"(a[2][0]),
+                     "+v"(a[2][1]), "+v"(a[3][0]), "+v"(a[3][1])::"memory");
+      // ---- top: hidden unit (d, half 0) has landed ----
+      asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+      asm volatile("s_barrier" ::: "memory");   // ... for every wave; all are done with slab d-1
 #pragma unroll
       for (int half = 0; half < 2; ++half) {
         if (half == 1) {
-          // ---- middle: hidden unit (d_idx, half 1) has landed (the six loads issued since
-          // the top may stay in flight) ----
-          asm volatile("s_waitcnt vmcnt(6)" ::: "memory");
-          asm volatile("s_barrier" ::: "memory");             // all are done with unit (d_idx, half 0)
+          // ---- middle: W(d+1) and hidden unit (d, half 1) have landed ----
+          asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+          asm volatile("s_barrier" ::: "memory");             // all are done with unit (d, half 0)
         }
         const uint32_t hb = lds0 + kHRing + hring * kSlab;
         hring = hring + 1 == kNH ? 0 : hring + 1;
@@ -502,22 +511,14 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
         u32x4 b[4][2];
 #pragma unroll
         for (int k16 = 0; k16 < 4; ++k16) {
-          if (half == 0 && k16 == 2) {
-            // (the wait counter holds 15: the W operands and the first four reads are
-            // retired before the last four are issued)
-            asm volatile("s_waitcnt lgkmcnt(0)"
-                         : "+v"(a[0][0]), "+v"(a[0][1]), "+v"(a[1][0]), "+v"(a[1][1]), "+v"(a[2][0]),
-                           "+v"(a[2][1]), "+v"(a[3][0]), "+v"(a[3][1]), "+v"(b[0][0]), "+v"(b[0][1]),
-                           "+v"(b[1][0]), "+v"(b[1][1])::"memory");
-          }
           b[k16][0] = lds_read128<0>(hb + b_off[k16]);
           b[k16][1] = lds_read128<4096>(hb + b_off[k16]);
         }
 #pragma unroll
         for (int grp = 0; grp < 2; ++grp) {
-          if (grp == 0 && half == 1) {
+          if (grp == 0) {
             asm volatile("s_waitcnt lgkmcnt(4)" : "+v"(b[0][0]), "+v"(b[0][1]), "+v"(b[1][0]), "+v"(b[1][1])::"memory");
-          } else if (grp == 1) {
+          } else {
             asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(b[2][0]), "+v"(b[2][1]), "+v"(b[3][0]), "+v"(b[3][1])::"memory");
           }
 #pragma unroll
@@ -527,26 +528,28 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
             const bf16x8 fb = __builtin_bit_cast(bf16x8, b[k16][m & 1]);
             acc[half][it][m & 1] = COPRIS_LM_MFMA(fa, fb, acc[half][it][m & 1]);
             // The twelve loads a wave issues per slab go out one at a time between the
-            // products (three per group of eight).  Issued in a bunch they keep every wave
-            // of the CU at the issue stage while the address unit works through them, and the
-            // matrix pipes idle meanwhile; spread out they cost the products nothing.
-            // Order: W slab d+1, hidden (d+1, half 0) (its slot and that slab's are free since
-            // the top barrier), then hidden (d+1, half 1) after the middle barrier has freed
-            // the slot of (d, half 0).  Past the last slab the loads re-read clamped rows into
-            // ring slots nobody reads any more.
-            if (m == 1 || m == 4 || m == 6) {
-              const int q = 3 * (2 * half + grp) + (m == 1 ? 0 : m == 4 ? 1 : 2);   // 0 .. 11
+            // products.  Issued in a bunch they keep every wave of the CU at the issue stage
+            // while the address unit works through them, and the matrix pipes idle meanwhile;
+            // spread out they cost the products nothing.  First half: hidden (d+1, half 0) (its
+            // slot is free since the top barrier), then W(d+2) (likewise); second half: hidden
+            // (d+1, half 1) (the middle barrier has freed the slot of (d, half 0)).  Past the
+            // last slab the loads re-read clamped rows into ring slots nobody reads any more.
+            if (half == 0 && (m & 1)) {
+              const int q = 4 * grp + (m >> 1);                                   // 0 .. 7
               __builtin_amdgcn_sched_barrier(0);
               if (q < 4) {
-                w_load(q);
-                if (q == 3) w_advance();
-              } else if (q < 8) {
-                h_load(q - 4);
-                if (q == 7) h_advance();
+                h_load(q);
+                if (q == 3) h_advance();
               } else {
-                h_load(q - 8);
-                if (q == 11) h_advance();
+                w_load(q - 4);
+                if (q == 7) w_advance();
               }
+              __builtin_amdgcn_sched_barrier(0);
+            } else if (half == 1 && (m == 1 || m == 5)) {
+              const int q = 2 * grp + (m >> 2);                                   // 0 .. 3
+              __builtin_amdgcn_sched_barrier(0);
+              h_load(q);
+              if (q == 3) h_advance();
               __builtin_amdgcn_sched_barrier(0);
             }
           }
