@@ -381,9 +381,10 @@ class RolloutManager:
             raise CoprisError(k, "copris_rollout_begin_stage")
         return k
 
-    def next_step(self):
+    def next_step(self, copy: bool = True):
         """Returns (code, plan): code is ROLLOUT_STEP / ROLLOUT_STAGE_END / ROLLOUT_EXHAUSTED; plan is a
-        dict of numpy copies of the manager's arrays (None unless code is ROLLOUT_STEP)."""
+        dict of the manager's arrays (None unless code is ROLLOUT_STEP): numpy copies, or with
+        copy=False views of the manager's own memory that are valid until the next call."""
         import numpy as np
         plan = RolloutPlan()
         code = load_library().copris_rollout_next_step(self._h, ctypes.addressof(plan))
@@ -391,7 +392,12 @@ class RolloutManager:
             raise CoprisError(code, "copris_rollout_next_step")
         if code != ROLLOUT_STEP:
             return code, None
-        arr = lambda ptr, n: np.ctypeslib.as_array(ptr, shape=(n,)).copy() if n else np.zeros(0, np.int32)
+
+        def arr(ptr, n):
+            if not n:
+                return np.zeros(0, np.int32)
+            a = np.ctypeslib.as_array(ptr, shape=(n,))
+            return a.copy() if copy else a
         return code, {
             "stage": plan.stage, "n_active": plan.n_active,
             "slot_traj": arr(plan.slot_traj, self.pool),

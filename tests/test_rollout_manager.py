@@ -219,3 +219,34 @@ def test_stepwise_bad_arguments_and_protocol():
     assert m.next_step()[0] == binding.ROLLOUT_STAGE_END
     assert m.end_stage()["batch_tokens"] == 3
     assert m.begin_stage() == 1 and m.next_step()[0] == binding.ROLLOUT_EXHAUSTED
+
+
+def test_stepwise_equals_the_event_driven_schedule_at_the_paper_settings():
+    # Table 4: pool 1024, 64 inputs x 8 samples per step, response lengths of the 7B-shaped
+    # recipe, 8 stages (about 15 000 decode steps): too long for the oracle's simulation, so the
+    # two implementations in the library - one jumps from finish event to finish event, the other
+    # advances a step at a time - are held against each other (they share only the trajectory
+    # record)
+    cfg = W.DECODE_CONFIGS[2]
+    rng = np.random.default_rng(11)
+    I, N, B, pool, stages = 64 * 16, 8, 64, 1024, 8
+    r = np.minimum(np.maximum(np.rint(rng.lognormal(7.5, 1.1, size=(I, N))), 1), 16384).astype(np.int32)
+    p = np.full(I, cfg.prompt, dtype=np.int32)
+    ref = binding.rollout_schedule(p, r, pool, B, max_stages=stages)
+    m = binding.RolloutManager(p, r, pool, B)
+    got = []
+    for k in range(stages):
+        assert m.begin_stage() == k
+        steps = 0
+        while True:
+            code, plan = m.next_step(copy=False)
+            if code != binding.ROLLOUT_STEP:
+                break
+            steps += 1
+            assert plan["n_active"] == pool          # fixed concurrency: the pool never idles here
+        assert code == binding.ROLLOUT_STAGE_END
+        st = m.end_stage()
+        assert st["steps"] == steps
+        got.append(st)
+    m.close()
+    _same(got, ref)
