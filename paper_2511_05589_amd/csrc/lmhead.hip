@@ -344,7 +344,11 @@ __device__ __forceinline__ u32x4 lds_read128(uint32_t addr) {
 #define COPRIS_LM_MFMA(fa, fb, c) __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa, fb, c, 0, 0, 0)
 #endif
 
-template <bool GIVEN>
+// HALVES = 2: 256 batch rows per workgroup (two halves of 128 against every W slab), W ring
+// of two slabs, hidden ring of three units.  HALVES = 1 (C <= 128): only the first half
+// exists, so there is no second half of products, loads and barrier; the hidden ring needs two
+// units and the W ring gets three slabs (a slab is requested two slabs ahead).
+template <bool GIVEN, int HALVES>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void lmhead_mfma_kernel(
     const uint16_t* __restrict__ hidden, const uint16_t* __restrict__ weight,
     const int64_t* __restrict__ seq_id, const int32_t* __restrict__ step,
@@ -359,6 +363,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   const int nkd = H / kMfBK;                   // slabs per tile
   const uint32_t lds0 = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(smem));
   const uint32_t pitch = static_cast<uint32_t>(H) * 2u;
+  constexpr int kRingW = HALVES == 2 ? kNW : 3;        // W ring slabs
+  constexpr int kRingH = HALVES == 2 ? kNH : 2;        // hidden ring units
+  constexpr int kHBase = kRingW * kSlab;               // hidden ring starts here
+  static_assert(kHBase + kRingH * kSlab <= kMfLds, "rings exceed the workgroup's LDS");
 
   // operand read offsets inside a slab / unit (bytes); it / nt add 32 rows = 4096 bytes
   uint32_t a_off[4], b_off[4];
@@ -401,16 +409,16 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 #endif
   };
   auto w_advance = [&]() __attribute__((always_inline)) {
-    w_ring = w_ring + 1 == kNW ? 0 : w_ring + 1;
+    w_ring = w_ring + 1 == kRingW ? 0 : w_ring + 1;
     if (++w_kd == nkd) {
       w_kd = 0;
       w_tile += gridDim.x;
     }
   };
   auto h_load = [&](int j) __attribute__((always_inline)) {
-    char* dst = smem + kHRing + h_ring * kSlab + (4 * wave + j) * 1024;
+    char* dst = smem + kHBase + h_ring * kSlab + (4 * wave + j) * 1024;
     const uint32_t koff = static_cast<uint32_t>(h_kd) * (kMfBK * 2) + ld_g;
-    const int c = min(c0 + 128 * (h_n & 1) + ld_row + 8 * j, C - 1);
+    const int c = min(c0 + (HALVES == 2 ? 128 * (h_n & 1) : 0) + ld_row + 8 * j, C - 1);
 #if !defined(COPRIS_LM_PROBE_NO_H_LOADS)
     __builtin_amdgcn_global_load_lds(hbase + (static_cast<uint32_t>(c) * pitch + (koff ^ ((j & 1) * 64))), dst,
                                      16, 0, 0);
@@ -419,8 +427,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 #endif
   };
   auto h_advance = [&]() __attribute__((always_inline)) {
-    h_ring = h_ring + 1 == kNH ? 0 : h_ring + 1;
-    if ((h_n & 1) && ++h_kd == nkd) h_kd = 0;
+    h_ring = h_ring + 1 == kRingH ? 0 : h_ring + 1;
+    if ((HALVES == 1 || (h_n & 1)) && ++h_kd == nkd) h_kd = 0;
     ++h_n;
   };
   auto issue_w = [&]() __attribute__((always_inline)) {
@@ -459,12 +467,22 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   // top of slab d the wave may leave its newest eight loads (W(d+1), hidden (d, 1)) in flight
   // and knows hidden (d, 0) has landed; at mid-slab it may leave the eight issued since the
   // top and knows W(d+1) and hidden (d, 1) have.
+  // (HALVES = 1: per slab d hidden (d+1), W(d+3); at the top of slab d the newest four loads,
+  // W(d+2), may stay in flight and hidden (d), W(d+1) have landed.)
   if (total > 0) {
-    issue_w();
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // W(0): the first slab reads it before any barrier of the loop
-    issue_h();
-    issue_w();
-    issue_h();
+    if (HALVES == 2) {
+      issue_w();
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // W(0): the first slab reads it before any barrier of the loop
+      issue_h();
+      issue_w();
+      issue_h();
+    } else {
+      issue_w();
+      issue_w();
+      issue_h();
+      issue_w();
+      asm volatile("s_waitcnt vmcnt(12)" ::: "memory");  // W(0)
+    }
   }
   asm volatile("s_barrier" ::: "memory");
 
@@ -477,6 +495,59 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i >> 2][(i >> 1) & 1][i & 1][r] = 0.0f;
 
+    if constexpr (HALVES == 1) {
+      for (int kd = 0; kd < nkd; ++kd) {
+        const uint32_t wb = lds0 + ring * kSlab;
+        ring = ring + 1 == kRingW ? 0 : ring + 1;
+        u32x4 a[4][2];
+#pragma unroll
+        for (int k16 = 0; k16 < 4; ++k16) {
+          a[k16][0] = lds_read128<0>(wb + a_off[k16]);
+          a[k16][1] = lds_read128<4096>(wb + a_off[k16]);
+        }
+        asm volatile("s_waitcnt lgkmcnt(0)"
+                     : "+v"(a[0][0]), "+v"(a[0][1]), "+v"(a[1][0]), "+v"(a[1][1]), "+v"(a[2][0]),
+                       "+v"(a[2][1]), "+v"(a[3][0]), "+v"(a[3][1])::"memory");
+        // ---- top: hidden unit (d) and W(d+1) have landed; every wave holds W(d)'s operands ----
+        asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+        asm volatile("s_barrier" ::: "memory");
+        const uint32_t hb = lds0 + kHBase + hring * kSlab;
+        hring = hring + 1 == kRingH ? 0 : hring + 1;
+        u32x4 b[4][2];
+#pragma unroll
+        for (int k16 = 0; k16 < 4; ++k16) {
+          b[k16][0] = lds_read128<0>(hb + b_off[k16]);
+          b[k16][1] = lds_read128<4096>(hb + b_off[k16]);
+        }
+#pragma unroll
+        for (int grp = 0; grp < 2; ++grp) {
+          if (grp == 0) {
+            asm volatile("s_waitcnt lgkmcnt(4)" : "+v"(b[0][0]), "+v"(b[0][1]), "+v"(b[1][0]), "+v"(b[1][1])::"memory");
+          } else {
+            asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(b[2][0]), "+v"(b[2][1]), "+v"(b[3][0]), "+v"(b[3][1])::"memory");
+          }
+#pragma unroll
+          for (int m = 0; m < 8; ++m) {
+            const int k16 = 2 * grp + (m >> 2), it = (m >> 1) & 1;
+            const bf16x8 fa = __builtin_bit_cast(bf16x8, a[k16][it]);
+            const bf16x8 fb = __builtin_bit_cast(bf16x8, b[k16][m & 1]);
+            acc[0][it][m & 1] = COPRIS_LM_MFMA(fa, fb, acc[0][it][m & 1]);
+            if (m & 1) {   // hidden (d+1) into the slot of (d-1), then W(d+3) into the slot of W(d)
+              const int q = 4 * grp + (m >> 1);                                   // 0 .. 7
+              __builtin_amdgcn_sched_barrier(0);
+              if (q < 4) {
+                h_load(q);
+                if (q == 3) h_advance();
+              } else {
+                w_load(q - 4);
+                if (q == 7) w_advance();
+              }
+              __builtin_amdgcn_sched_barrier(0);
+            }
+          }
+        }
+      }
+    } else
     for (int kd = 0; kd < nkd; ++kd) {
       // The W operands of the slab go to registers BEFORE the top barrier (the slab has been
       // in LDS, for every wave, since the middle barrier of the slab before), so that barrier
@@ -504,8 +575,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
           asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
           asm volatile("s_barrier" ::: "memory");             // all are done with unit (d, half 0)
         }
-        const uint32_t hb = lds0 + kHRing + hring * kSlab;
-        hring = hring + 1 == kNH ? 0 : hring + 1;
+        const uint32_t hb = lds0 + kHBase + hring * kSlab;
+        hring = hring + 1 == kRingH ? 0 : hring + 1;
         // all eight hidden operands of the half at once, then sixteen products in two groups
         // of eight: one wait per eight products instead of one per four
         u32x4 b[4][2];
@@ -583,8 +654,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     };
     epilogue(std::integral_constant<int, 0>{});
     epilogue(std::integral_constant<int, 1>{});
-    epilogue(std::integral_constant<int, 2>{});
-    epilogue(std::integral_constant<int, 3>{});
+    if (HALVES == 2) {
+      epilogue(std::integral_constant<int, 2>{});
+      epilogue(std::integral_constant<int, 3>{});
+    }
   }
 
   // lane state -> partial; combine the two k-halves of a wave, then the two vocabulary
@@ -961,15 +1034,16 @@ static int launch_lmhead(const void* hidden, const void* weight, const int64_t* 
     const int n_tiles = (V + kMfBM - 1) / kMfBM;
     const dim3 grid(n_parts, (C + kMfBN - 1) / kMfBN);
     COPRIS_PRE("lmhead_mfma_kernel");
-    if (given) {
-      hipLaunchKernelGGL(lmhead_mfma_kernel<true>, grid, dim3(256), 0, stream,
-                         static_cast<const uint16_t*>(hidden), static_cast<const uint16_t*>(weight),
-                         seq_id, step, target, key0, key1, inv_t, part, C, H, V, n_tiles, n_parts);
-    } else {
-      hipLaunchKernelGGL(lmhead_mfma_kernel<false>, grid, dim3(256), 0, stream,
-                         static_cast<const uint16_t*>(hidden), static_cast<const uint16_t*>(weight),
-                         seq_id, step, target, key0, key1, inv_t, part, C, H, V, n_tiles, n_parts);
-    }
+#define COPRIS_LM_MFMA_LAUNCH(G, HV)                                                                   \
+  hipLaunchKernelGGL((lmhead_mfma_kernel<G, HV>), grid, dim3(256), 0, stream,                            \
+                     static_cast<const uint16_t*>(hidden), static_cast<const uint16_t*>(weight), seq_id, \
+                     step, target, key0, key1, inv_t, part, C, H, V, n_tiles, n_parts)
+    const bool one_half = C <= kMfBN / 2;      // only the first 128 batch rows exist
+    if (given && one_half) COPRIS_LM_MFMA_LAUNCH(true, 1);
+    else if (given) COPRIS_LM_MFMA_LAUNCH(true, 2);
+    else if (one_half) COPRIS_LM_MFMA_LAUNCH(false, 1);
+    else COPRIS_LM_MFMA_LAUNCH(false, 2);
+#undef COPRIS_LM_MFMA_LAUNCH
     COPRIS_POST("lmhead_mfma_kernel");
   } else {
     const dim3 grid(n_parts, (C + kLmTileC - 1) / kLmTileC);
