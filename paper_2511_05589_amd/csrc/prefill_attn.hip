@@ -3,12 +3,18 @@
 // (Section 4, "Prioritized Resumption": buffered partial trajectories are continued in the
 // next rollout stage; Section 5.3 names their re-prefilling as a cost of high concurrency).
 //
-// bf16, head_dim 128, page 16.  One workgroup owns (sequence, kv head, tile of 32 query
-// tokens); wave h of it owns query head kvh*g + h for those 32 tokens, as two blocks of 16
-// queries.  The workgroup walks the sequence's K/V in 32-token steps (two pages) up to the
-// tile's own tokens, which are the last step; a step's K and V rows (2 x 8 KB) are fetched
-// once by all waves together, register-staged two steps ahead, parked in a double-buffered
-// LDS tile and read by every wave in operand layout.  Per block of 16 queries:
+// bf16, head_dim 128, page 16.  One workgroup of four waves owns (sequence, kv head, up to
+// four of the kv head's query heads, tile of 32 query tokens); wave h of it owns one query head
+// for those 32 tokens, as two blocks of 16 queries.  A group of more than four query heads per
+// kv head is spread evenly over two workgroups, which fetch the K/V rows each on their own: a
+// step of one wave is a chain (scores -> weights -> value product) that no second wave of the
+// same workgroup can overlap, because they all pass the same barrier, so the matrix pipes are
+// kept busy by TWO independent workgroups per CU whose chains drift apart.
+// The workgroup walks the sequence's K/V in 32-token steps (two pages) up to the tile's own
+// tokens, which are the last step; a step's K and V rows (2 x 8 KB) are fetched once by all
+// waves together with LDS-direct loads, three steps ahead, into a ring of four LDS buffers
+// (the XOR swizzle is applied by choosing which global granule a lane fetches) and read by
+// every wave in operand layout.  Per block of 16 queries:
 //     S^T[token][query] = K[token][:] . Q[query][:]           2 x 4 x mfma 16x16x32 (16 tokens each)
 //     O^T[d][query]    += V^T[d][token] . P^T[token][query]   8 x mfma 16x16x32 (all 32 tokens)
 // The value product runs over the step's 32 tokens at once (the 32-deep instruction has
@@ -18,9 +24,12 @@
 // operands are two register pairs put side by side, nothing moves between lanes.
 // The K and V operands are read from LDS once per step and used for both query blocks,
 // and max / sum / rescale of a query live in the lane that owns it.  Only the last step
-// needs the causal mask.  The workgroup that owns a tile also writes
+// needs the causal mask.  The first workgroup of a (sequence, kv head, tile) also copies
 // that tile's K/V rows to the sequence's pages (each row is written by exactly one
 // workgroup).  Tiles are taken from the end of the sequences first (the long ones).
+//
+// LDS reads are inline instructions with explicit waits: the compiler cannot tell which
+// LDS-direct load fills which buffer and would wait for all of them before any LDS read.
 #include <type_traits>
 
 #include "copris_device.h"
@@ -43,10 +52,18 @@ constexpr int kPageGranules = kP * kD * 2 / 16;   // 256 16-byte granules of K (
 constexpr int kSubs = 2;                          // pages per step
 constexpr int kStepTok = kSubs * kP;              // 32 tokens per step (= kTileQ: a tile's own tokens are one step)
 constexpr int kStepGranules = kSubs * kPageGranules;   // 512 granules of K (and of V) per step
+constexpr int kHalfBytes = kStepGranules * 16;    // 8 KB: a step's K rows (or V rows)
+constexpr int kBufBytes = 2 * kHalfBytes;         // 16 KB: one ring buffer = K rows, then V rows
+constexpr int kRing = 4;                          // ring buffers
+constexpr int kAhead = kRing - 1;                 // a step is requested this many steps before its use
+constexpr int kThreads = 256;                     // four waves; the first `nheads` compute, all fetch
+constexpr int kHeadsPerWg = kThreads / 64;
+constexpr int kLoadsPerStep = 2 * kStepGranules / kThreads;   // LDS-direct loads a wave issues per step
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 constexpr float kSlack = 6.0f;   // scores may exceed the softmax reference by 2^kSlack
 constexpr float kBig = 64.0f;    // = 2^kSlack
+static_assert(kLoadsPerStep == 4, "the waits below count four loads per wave and step");
 
 __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
   uint32_t r;
@@ -54,30 +71,39 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
   return r;
 }
 
-// LDS position (in 16-byte granules) of granule c of token row `row` (conflict-free for the
-// row-wise writes and for both operand read patterns).
+// LDS position (in 16-byte granules) of granule c of token row `row` of a page (conflict-free
+// for the row-wise fills and for both operand read patterns).
 __device__ __forceinline__ int swz_k(int row, int c) { return row * 16 + (c ^ (row & 15)); }
 __device__ __forceinline__ int swz_v(int row, int c) { return row * 16 + (c ^ ((row & 7) << 1)); }
 
-// Threads of a workgroup: four or eight waves (they divide the 1024 granules of a step
-// evenly and keep the staging registers few); the first G compute, all fetch.
-template <int G> struct PrefillThreads {
-  static constexpr int value = G <= 4 ? 256 : 512;
-};
+template <int OFF>
+__device__ __forceinline__ u32x4 lds_read128(uint32_t addr) {
+  u32x4 x;
+  asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(x) : "v"(addr), "n"(OFF) : "memory");
+  return x;
+}
+// the transposing read: four 16-bit elements of four rows, delivered in MFMA operand order
+template <int OFF>
+__device__ __forceinline__ s16x4 lds_read_tr16(uint32_t addr) {
+  s16x4 x;
+  asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(x) : "v"(addr), "n"(OFF) : "memory");
+  return x;
+}
 
-template <int G>
-__global__ __launch_bounds__(PrefillThreads<G>::value) void prefill_attn_kernel(
+// (two workgroups per CU: 256 registers per lane)
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) void prefill_attn_kernel(
     const uint16_t* __restrict__ q, const u32x4* __restrict__ k, const u32x4* __restrict__ v,
     const int32_t* __restrict__ cu_seqlens, const int32_t* __restrict__ block_table,
     u32x4* __restrict__ k_cache, u32x4* __restrict__ v_cache, uint16_t* __restrict__ out,
-    float* __restrict__ lse, int Hq, int Hkv, int max_pages, float scale_log2e) {
-  constexpr int kThreads = PrefillThreads<G>::value;
-  constexpr int kStage = 2 * kStepGranules / kThreads;   // granules a thread moves per step
-  static_assert(kStage * kThreads == 2 * kStepGranules, "a step's granules divide evenly over the threads");
-  __shared__ u32x4 lds_k[2][kStepGranules];
-  __shared__ u32x4 lds_v[2][kStepGranules];
+    float* __restrict__ lse, int Hq, int Hkv, int n_groups, int max_pages, float scale_log2e) {
+  __shared__ __attribute__((aligned(1024))) char smem[kRing * kBufBytes];
 
-  const int b = blockIdx.z, kvh = blockIdx.y;
+  const int b = blockIdx.z;
+  const int kvh = static_cast<int>(blockIdx.y) / n_groups, hg = static_cast<int>(blockIdx.y) % n_groups;
+  // this workgroup's query heads of the kv head: g heads spread evenly over n_groups workgroups
+  const int g = Hq / Hkv;
+  const int nheads = g / n_groups + (hg < g % n_groups ? 1 : 0);
+  const int head0 = hg * (g / n_groups) + min(hg, g % n_groups);
   const int s0 = cu_seqlens[b];
   const int len = cu_seqlens[b + 1] - s0;
   const int n_tiles = (len + kTileQ - 1) / kTileQ;
@@ -87,12 +113,28 @@ __global__ __launch_bounds__(PrefillThreads<G>::value) void prefill_attn_kernel(
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int n = lane & 15;        // N index of both products: the query within a block
   const int bq = lane >> 4;       // k-group of the MFMA operand layouts
-  const bool computes = wave < G;                 // (the other waves only move data)
-  const int head = kvh * G + min(wave, G - 1);
+  const bool computes = wave < nheads;            // (the other waves only move data)
+  const int head = kvh * g + head0 + min(wave, nheads - 1);
   const int q0 = tile * kTileQ;                      // first query token of the tile
-  const int last_step = tile;                        // the tile's own tokens
-  const int last_page = (len - 1) / kP;
-  const int32_t* bt = block_table + static_cast<size_t>(b) * max_pages;
+  const uint32_t lds0 = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(smem));
+
+  // ---- the tile's own K/V rows go to the sequence's pages (slots past the end of the
+  // sequence are left alone) ----
+  if (hg == 0) {
+    const int32_t* bt = block_table + static_cast<size_t>(b) * max_pages;
+#pragma unroll
+    for (int j = 0; j < 2 * kStepGranules / kThreads; ++j) {
+      const int i = tid + j * kThreads;             // i < 512: K, else V; token (i & 511) >> 4, granule i & 15
+      const int gi = i & (kStepGranules - 1);
+      const int tok = q0 + (gi >> 4);
+      if (tok < len) {
+        const size_t src = (static_cast<size_t>(s0 + tok) * Hkv + kvh) * (kD * 2 / 16) + (gi & 15);
+        const size_t dst = (static_cast<size_t>(bt[tok / kP]) * Hkv + kvh) * kPageGranules + (gi & (kPageGranules - 1));
+        if (i < kStepGranules) k_cache[dst] = k[src];
+        else v_cache[dst] = v[src];
+      }
+    }
+  }
 
   // Q^T operands: lane (n, bq) holds Q[query n of block nb][32*kk + 8*bq .. +8]; queries past
   // the end of the sequence are zero
@@ -110,90 +152,104 @@ __global__ __launch_bounds__(PrefillThreads<G>::value) void prefill_attn_kernel(
     }
   }
 
-  // ---- cooperative, register-staged fetch of one step (32 tokens of K and of V) ----
-  // granule i of a step: i < 512 is K, else V; token (i & 511) >> 4, column granule i & 15.
-  // Rows past the end of the sequence re-read its last row (they are masked below).
-  // two register stages: the fetch of step s+2 is in flight while step s+1 is parked
-  u32x4 stage_a[kStage], stage_b[kStage];
-  auto fetch = [&](u32x4 (&stage)[kStage], int step) __attribute__((always_inline)) {
-    // steps past the last one re-read the last token's rows (never parked)
+  // ---- LDS-direct fetch of one step (32 tokens of K and of V) into a ring buffer ----
+  // A wave moves rows 8*wave .. 8*wave+7 of K and of V: per operand two instructions of four
+  // rows x 256 bytes.  LDS position lane%16 of row 8*wave + 4*j + lane/16 takes the global
+  // granule that the swizzle maps there.  Rows past the end of the sequence re-read its last
+  // row (they are masked below); steps past the last one do the same into buffers nobody reads.
+  const int ld_row = 8 * wave + (lane >> 4);                       // + 4*j
+  const size_t row_pitch = static_cast<size_t>(Hkv) * (kD * 2);
+  const char* kbase = reinterpret_cast<const char*>(k) + (static_cast<size_t>(s0) * Hkv + kvh) * (kD * 2);
+  const char* vbase = reinterpret_cast<const char*>(v) + (static_cast<size_t>(s0) * Hkv + kvh) * (kD * 2);
+  uint32_t ld_gk[2], ld_gv[2];                                     // byte offset of the lane's granule in its row
+  uint32_t ld_ok[2], ld_ov[2];                                     // ... and in a whole step, for steps that need no clamp
 #pragma unroll
-    for (int j = 0; j < kStage; ++j) {
-      const int i = tid + j * kThreads;
-      const int tok = min(step * kStepTok + ((i & (kStepGranules - 1)) >> 4), len - 1);
-      const size_t g = (static_cast<size_t>(s0 + tok) * Hkv + kvh) * (kD * 2 / 16) + (i & 15);
-      const u32x4* src = (i < kStepGranules) ? k : v;
-      stage[j] = src[g];
-    }
-  };
-  // park the staged step in LDS buffer `buf` (page-sized halves, each swizzled on its own);
-  // the step of the tile's own tokens also goes to the sequence's pages (slots past the end
-  // of the sequence are left alone)
-  auto park = [&](u32x4 (&stage)[kStage], int step, int buf, auto may_own) __attribute__((always_inline)) {
-    const bool own = decltype(may_own)::value && step == tile;
+  for (int j = 0; j < 2; ++j) {
+    const int row = ld_row + 4 * j;
+    ld_gk[j] = static_cast<uint32_t>((lane & 15) ^ (row & 15)) * 16;
+    ld_gv[j] = static_cast<uint32_t>((lane & 15) ^ ((row & 7) << 1)) * 16;
+    ld_ok[j] = static_cast<uint32_t>(row) * static_cast<uint32_t>(row_pitch) + ld_gk[j];
+    ld_ov[j] = static_cast<uint32_t>(row) * static_cast<uint32_t>(row_pitch) + ld_gv[j];
+  }
+  auto fetch = [&](int step) __attribute__((always_inline)) {
+    char* dst = smem + (step & (kRing - 1)) * kBufBytes + (8 * wave) * 256;
+    if (step * kStepTok + kStepTok <= len) {
+      // a whole step inside the sequence: one address for the wave plus the lane's fixed offset
+      const size_t so = static_cast<size_t>(step) * kStepTok * row_pitch;
 #pragma unroll
-    for (int j = 0; j < kStage; ++j) {
-      const int i = tid + j * kThreads;
-      const int gi = i & (kStepGranules - 1), sub = gi >> 8, tok = (gi >> 4) & 15, c = gi & 15;
-      const bool live = own && step * kStepTok + sub * kP + tok < len;
-      // (the table entry of a page past the sequence's last one is never read)
-      const size_t page =
-          own ? (static_cast<size_t>(bt[min(kSubs * step + sub, last_page)]) * Hkv + kvh) * kPageGranules : 0;
-      if (i < kStepGranules) {
-        lds_k[buf][sub * kPageGranules + swz_k(tok, c)] = stage[j];
-        if (live) k_cache[page + (gi & (kPageGranules - 1))] = stage[j];
-      } else {
-        lds_v[buf][sub * kPageGranules + swz_v(tok, c)] = stage[j];
-        if (live) v_cache[page + (gi & (kPageGranules - 1))] = stage[j];
+      for (int j = 0; j < 2; ++j) {
+        __builtin_amdgcn_global_load_lds(kbase + so + ld_ok[j], dst + j * 1024, 16, 0, 0);
+        __builtin_amdgcn_global_load_lds(vbase + so + ld_ov[j], dst + kHalfBytes + j * 1024, 16, 0, 0);
+      }
+    } else {
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        const int tok = min(step * kStepTok + ld_row + 4 * j, len - 1);
+        const size_t ro = static_cast<size_t>(tok) * row_pitch;
+        __builtin_amdgcn_global_load_lds(kbase + (ro + ld_gk[j]), dst + j * 1024, 16, 0, 0);
+        __builtin_amdgcn_global_load_lds(vbase + (ro + ld_gv[j]), dst + kHalfBytes + j * 1024, 16, 0, 0);
       }
     }
   };
+
+  // operand read addresses inside a ring buffer (bytes)
+  uint32_t k_off[4], v_off[8];
+#pragma unroll
+  for (int kk = 0; kk < 4; ++kk) k_off[kk] = lds0 + swz_k(n, 4 * kk + bq) * 16;
+  {
+    const int vrow = 4 * bq + (n >> 2);
+#pragma unroll
+    for (int dt = 0; dt < 8; ++dt)
+      v_off[dt] = lds0 + kHalfBytes + swz_v(vrow, 2 * dt + ((n & 3) >> 1)) * 16 + (n & 1) * 8;
+  }
 
   float m_run[2] = {-INFINITY, -INFINITY}, l_run[2] = {0.0f, 0.0f};
   f32x4 o[2][8];
 #pragma unroll
   for (int i = 0; i < 16; ++i) o[i >> 3][i & 7] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
 
-  fetch(stage_a, 0);
-  fetch(stage_b, 1);
-  park(stage_a, 0, 0, std::true_type{});
-  __syncthreads();
+  // A wave's loads complete in issue order, four per step: once at most 4*(kAhead-1) are
+  // outstanding, the step after the current one has landed.
+#pragma unroll
+  for (int st = 0; st < kAhead; ++st) fetch(st);
+  asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(4 * (kAhead - 1)) : "memory");
 
-  // one step; `cur` holds the rows of step+1 (fetched a step ago), `nxt` is free and takes
-  // the fetch of step+2 (unconditional: a fetch past the end stays in bounds and is dropped)
-  // diag = false: a step strictly before the tile's own tokens whose successor is not the
-  // tile's own step either (no mask, no page write, and the step after it exists)
-  auto do_step = [&](u32x4 (&cur)[kStage], u32x4 (&nxt)[kStage], const int step, auto diag) __attribute__((always_inline)) {
+  // one step.  diag = true: the tile's own tokens (causal mask, end of the sequence)
+  auto do_step = [&](const int step, auto diag) __attribute__((always_inline)) {
     constexpr bool kDiag = decltype(diag)::value;
-    const int buf = step & 1;
-    fetch(nxt, step + 2);
+    const uint32_t boff = static_cast<uint32_t>(step & (kRing - 1)) * kBufBytes;
+    fetch(step + kAhead);          // into the buffer of step-1, which every wave left at the last barrier
 
     if (computes) {
-      const bool tail = kDiag && step * kStepTok + kStepTok > len;  // tokens past the end of the sequence
       // Scores of the two pages: K rows as the A operand (token = lane & 15), read once for
       // both query blocks.  This lane: query n of each block, tokens 4*bq .. 4*bq+3 of each page.
       // A block whose queries all lie before a page's tokens is fully masked there: its
       // weights are exp2(-inf - m) = 0 (m is finite from step 0 on: token 0 is visible to
       // every query).
       float t[kSubs][2][4];
+      u32x4 kf[kSubs][4];
+#pragma unroll
+      for (int kk = 0; kk < 4; ++kk) kf[0][kk] = lds_read128<0>(boff + k_off[kk]);
+#pragma unroll
+      for (int kk = 0; kk < 4; ++kk) kf[1][kk] = lds_read128<kPageGranules * 16>(boff + k_off[kk]);
 #pragma unroll
       for (int sub = 0; sub < kSubs; ++sub) {
-        if (sub > 0) __builtin_amdgcn_sched_barrier(0);   // (one page's K operands in registers at a time)
-        bf16x8 kf[4];
-#pragma unroll
-        for (int kk = 0; kk < 4; ++kk)
-          kf[kk] = __builtin_bit_cast(bf16x8, lds_k[buf][sub * kPageGranules + swz_k(n, 4 * kk + bq)]);
+        if (sub == 0) {
+          asm volatile("s_waitcnt lgkmcnt(4)" : "+v"(kf[0][0]), "+v"(kf[0][1]), "+v"(kf[0][2]), "+v"(kf[0][3])::"memory");
+        } else {
+          asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(kf[1][0]), "+v"(kf[1][1]), "+v"(kf[1][2]), "+v"(kf[1][3])::"memory");
+        }
 #pragma unroll
         for (int nb = 0; nb < 2; ++nb) {
           f32x4 sc = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
           for (int kk = 0; kk < 4; ++kk)
-            sc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[kk], qf[nb][kk], sc, 0, 0, 0);
+            sc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kf[sub][kk]), qf[nb][kk], sc, 0, 0, 0);
 #pragma unroll
           for (int rr = 0; rr < 4; ++rr) t[sub][nb][rr] = sc[rr];   // raw: the scale rides on the exponent's fma
         }
       }
-      if (kDiag && (step == tile || tail)) {           // the tile's own step, or one at the end
+      if (kDiag) {
 #pragma unroll
         for (int sub = 0; sub < kSubs; ++sub)
 #pragma unroll
@@ -205,6 +261,15 @@ __global__ __launch_bounds__(PrefillThreads<G>::value) void prefill_attn_kernel(
               t[sub][nb][rr] = (tk <= tq && tk < len) ? t[sub][nb][rr] : -INFINITY;
             }
           }
+      }
+      // V^T operands of the first four head-dim tiles are requested now and arrive during the
+      // softmax: as the A operand through the transposing read (per page the lane gets rows
+      // 4*bq + n/4 .. of columns 16*dt + 4*(n%4) .. +3), the two pages' halves side by side.
+      s16x4 vf[8][2];
+#pragma unroll
+      for (int dt = 0; dt < 4; ++dt) {
+        vf[dt][0] = lds_read_tr16<0>(boff + v_off[dt]);
+        vf[dt][1] = lds_read_tr16<kPageGranules * 16>(boff + v_off[dt]);
       }
       // The running reference m of a query only has to keep the weights in range, so it is
       // left alone while no score of the step exceeds it by more than kSlack (in log2 units):
@@ -260,49 +325,38 @@ __global__ __launch_bounds__(PrefillThreads<G>::value) void prefill_attn_kernel(
             bf16x8, u32x4{pack_bf16x2(w[nb][0][0], w[nb][0][1]), pack_bf16x2(w[nb][0][2], w[nb][0][3]),
                           pack_bf16x2(w[nb][1][0], w[nb][1][1]), pack_bf16x2(w[nb][1][2], w[nb][1][3])});
       }
-      // V^T as the A operand through the transposing read (per page the lane gets rows
-      // 4*bq + n/4 .. of columns 16*dt + 4*(n%4) .. +3): the two pages' halves side by side.
-      // (Read only now: held across the scores and the softmax the V operands would not fit
-      // in the register file beside the two staging sets.)
-      __builtin_amdgcn_sched_barrier(0);
-      {
-        const int vrow = 4 * bq + (n >> 2);
-        const char* vbase = reinterpret_cast<const char*>(lds_v[buf]) + (n & 1) * 8;
 #pragma unroll
-        for (int dt = 0; dt < 8; ++dt) {
-          const char* addr = vbase + swz_v(vrow, 2 * dt + ((n & 3) >> 1)) * 16;
-          const s16x4 v0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(addr));
-          const s16x4 v1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-              (__attribute__((address_space(3))) s16x4*)(addr + kPageGranules * 16));
+      for (int dt = 4; dt < 8; ++dt) {
+        vf[dt][0] = lds_read_tr16<0>(boff + v_off[dt]);
+        vf[dt][1] = lds_read_tr16<kPageGranules * 16>(boff + v_off[dt]);
+      }
+#pragma unroll
+      for (int half = 0; half < 2; ++half) {
+        if (half == 0) {
+          asm volatile("s_waitcnt lgkmcnt(8)"
+                       : "+v"(vf[0][0]), "+v"(vf[0][1]), "+v"(vf[1][0]), "+v"(vf[1][1]), "+v"(vf[2][0]),
+                         "+v"(vf[2][1]), "+v"(vf[3][0]), "+v"(vf[3][1])::"memory");
+        } else {
+          asm volatile("s_waitcnt lgkmcnt(0)"
+                       : "+v"(vf[4][0]), "+v"(vf[4][1]), "+v"(vf[5][0]), "+v"(vf[5][1]), "+v"(vf[6][0]),
+                         "+v"(vf[6][1]), "+v"(vf[7][0]), "+v"(vf[7][1])::"memory");
+        }
+#pragma unroll
+        for (int dt = 4 * half; dt < 4 * half + 4; ++dt) {
+          const s16x4 v0 = vf[dt][0], v1 = vf[dt][1];
           const s16x8 vv = {v0[0], v0[1], v0[2], v0[3], v1[0], v1[1], v1[2], v1[3]};
-          const bf16x8 vf = __builtin_bit_cast(bf16x8, vv);
-          o[0][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, pf[0], o[0][dt], 0, 0, 0);
-          o[1][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, pf[1], o[1][dt], 0, 0, 0);
+          const bf16x8 va = __builtin_bit_cast(bf16x8, vv);
+          o[0][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va, pf[0], o[0][dt], 0, 0, 0);
+          o[1][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va, pf[1], o[1][dt], 0, 0, 0);
         }
       }
     }
-    // park step+1; that LDS buffer was last read one step ago
-    if (kDiag) {
-      if (step < last_step) park(cur, step + 1, buf ^ 1, std::true_type{});
-    } else {
-      park(cur, step + 1, buf ^ 1, std::false_type{});
-    }
-    __syncthreads();
+    // the next step has landed, for every wave; all are done with this step's buffer
+    asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(4 * (kAhead - 1)) : "memory");
   };
-  int step = 0;
-  for (; step + 2 <= tile - 1; step += 2) {       // pairs of steps well before the tile's own
-    do_step(stage_b, stage_a, step, std::false_type{});
-    do_step(stage_a, stage_b, step + 1, std::false_type{});
-  }
-  for (; step <= last_step; ++step) {             // the last one to three steps, one code copy:
-    do_step(stage_b, stage_a, step, std::true_type{});
-#pragma unroll
-    for (int j = 0; j < kStage; ++j) {            // the two staging sets trade places
-      const u32x4 x = stage_a[j];
-      stage_a[j] = stage_b[j];
-      stage_b[j] = x;
-    }
-  }
+  for (int step = 0; step < tile; ++step) do_step(step, std::false_type{});
+  do_step(tile, std::true_type{});
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // (the loads past the last step land before the LDS is given back)
 
   // normalise and store: lane (n, bq) owns d = 16*dt + 4*bq + r of query n
 #pragma unroll
@@ -339,26 +393,15 @@ int launch_prefill_attn(const void* q, const void* k, const void* v, const int32
                         float* lse, int B, int Hq, int Hkv, int max_pages, int max_seqlen,
                         float scale, hipStream_t stream) {
   const int g = Hq / Hkv;
-  const dim3 grid((max_seqlen + kTileQ - 1) / kTileQ, Hkv, B);
+  const int n_groups = (g + kHeadsPerWg - 1) / kHeadsPerWg;
+  const dim3 grid((max_seqlen + kTileQ - 1) / kTileQ, Hkv * n_groups, B);
   const float scale_log2e = scale * kLog2e;
-#define COPRIS_PREFILL(G)                                                                        \
-  hipLaunchKernelGGL(prefill_attn_kernel<G>, grid, dim3(PrefillThreads<G>::value), 0, stream,    \
-                     static_cast<const uint16_t*>(q), static_cast<const u32x4*>(k),              \
-                     static_cast<const u32x4*>(v), cu_seqlens, block_table,                      \
-                     static_cast<u32x4*>(k_cache), static_cast<u32x4*>(v_cache),                 \
-                     static_cast<uint16_t*>(out), lse, Hq, Hkv, max_pages, scale_log2e)
   COPRIS_PRE("prefill_attn_kernel");
-  switch (g) {
-    case 1: COPRIS_PREFILL(1); break;
-    case 2: COPRIS_PREFILL(2); break;
-    case 3: COPRIS_PREFILL(3); break;
-    case 4: COPRIS_PREFILL(4); break;
-    case 5: COPRIS_PREFILL(5); break;
-    case 6: COPRIS_PREFILL(6); break;
-    case 7: COPRIS_PREFILL(7); break;
-    default: COPRIS_PREFILL(8); break;
-  }
-#undef COPRIS_PREFILL
+  hipLaunchKernelGGL(prefill_attn_kernel, grid, dim3(kThreads), 0, stream,
+                     static_cast<const uint16_t*>(q), static_cast<const u32x4*>(k),
+                     static_cast<const u32x4*>(v), cu_seqlens, block_table,
+                     static_cast<u32x4*>(k_cache), static_cast<u32x4*>(v_cache),
+                     static_cast<uint16_t*>(out), lse, Hq, Hkv, n_groups, max_pages, scale_log2e);
   COPRIS_POST("prefill_attn_kernel");
   return 0;
 }
