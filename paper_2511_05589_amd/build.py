@@ -58,6 +58,11 @@ def build(verbose: bool = False, lib_path: str = LIB_PATH, extra_flags=()) -> st
             j.result()
     _run([hipcc, "--offload-arch=gfx950", "-fPIC", "-shared", "-o", lib_path] + list(extra_flags) + objs,
          verbose)
+    if lib_path == LIB_PATH:
+        # the stand-alone chip-rate measurement (not part of the library) is compiled with it so
+        # that it keeps building
+        _run([hipcc, "--offload-arch=gfx950", "-O3", "-o", os.path.join(OBJ_DIR, "chip_rates"),
+              os.path.join(CSRC, "chip_rates.hip")], verbose)
     return lib_path
 
 
