@@ -3,15 +3,19 @@
 // (Section 4, "Prioritized Resumption": buffered partial trajectories are continued in the
 // next rollout stage; Section 5.3 names their re-prefilling as a cost of high concurrency).
 //
-// bf16, head_dim 128, page 16.  One workgroup of four waves owns (sequence, kv head, up to
-// four of the kv head's query heads, tile of 32 query tokens); wave h of it owns one query head
-// for those 32 tokens, as two blocks of 16 queries.  A group of more than four query heads per
-// kv head is spread evenly over two workgroups, which fetch the K/V rows each on their own: a
-// step of one wave is a chain (scores -> weights -> value product) that no second wave of the
+// bf16, head_dim 128, page 16.  The unit of work is (query head, tile of 32 query tokens): one
+// wave, the tile as two blocks of 16 queries.  A workgroup is four waves = four consecutive
+// units of one (sequence, kv head, super-tile of T tiles), the units numbered tile-major
+// (unit u = tile u / g, head u % g of the kv head's g query heads) and T = 4 / gcd(g, 4) so that
+// the units of a super-tile fill whole workgroups for every g: no wave is without a unit except
+// at the end of a sequence.  A workgroup's units lie in at most two neighbouring tiles (g >= 4),
+// so its waves need the same K/V rows: the workgroup walks the sequence's K/V once, up to
+// the last of its tiles, and a wave whose own tile is over only keeps fetching.
+// A step of one wave is a chain (scores -> weights -> value product) that no second wave of the
 // same workgroup can overlap, because they all pass the same barrier, so the matrix pipes are
 // kept busy by TWO independent workgroups per CU whose chains drift apart.
-// The workgroup walks the sequence's K/V in 32-token steps (two pages) up to the tile's own
-// tokens, which are the last step; a step's K and V rows (2 x 8 KB) are fetched once by all
+// The workgroup walks the K/V in 32-token steps (two pages); a wave's last step is its tile's
+// own tokens; a step's K and V rows (2 x 8 KB) are fetched once by all
 // waves together with LDS-direct loads, three steps ahead, into a ring of four LDS buffers
 // (the XOR swizzle is applied by choosing which global granule a lane fetches) and read by
 // every wave in operand layout.  Per block of 16 queries:
@@ -24,9 +28,9 @@
 // operands are two register pairs put side by side, nothing moves between lanes.
 // The K and V operands are read from LDS once per step and used for both query blocks,
 // and max / sum / rescale of a query live in the lane that owns it.  Only the last step
-// needs the causal mask.  The first workgroup of a (sequence, kv head, tile) also copies
+// needs the causal mask.  The workgroup that holds a tile's unit of head 0 also copies
 // that tile's K/V rows to the sequence's pages (each row is written by exactly one
-// workgroup).  Tiles are taken from the end of the sequences first (the long ones).
+// workgroup).  Super-tiles are taken from the end of the sequences first (the long ones).
 //
 // LDS reads are inline instructions with explicit waits: the compiler cannot tell which
 // LDS-direct load fills which buffer and would wait for all of them before any LDS read.
@@ -56,7 +60,7 @@ constexpr int kHalfBytes = kStepGranules * 16;    // 8 KB: a step's K rows (or V
 constexpr int kBufBytes = 2 * kHalfBytes;         // 16 KB: one ring buffer = K rows, then V rows
 constexpr int kRing = 4;                          // ring buffers
 constexpr int kAhead = kRing - 1;                 // a step is requested this many steps before its use
-constexpr int kThreads = 256;                     // four waves; the first `nheads` compute, all fetch
+constexpr int kThreads = 256;                     // four waves = four units; all fetch
 constexpr int kHeadsPerWg = kThreads / 64;
 constexpr int kLoadsPerStep = 2 * kStepGranules / kThreads;   // LDS-direct loads a wave issues per step
 constexpr float kLog2e = 1.4426950408889634f;
@@ -95,38 +99,46 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2))
     const uint16_t* __restrict__ q, const u32x4* __restrict__ k, const u32x4* __restrict__ v,
     const int32_t* __restrict__ cu_seqlens, const int32_t* __restrict__ block_table,
     u32x4* __restrict__ k_cache, u32x4* __restrict__ v_cache, uint16_t* __restrict__ out,
-    float* __restrict__ lse, int Hq, int Hkv, int n_groups, int max_pages, float scale_log2e) {
+    float* __restrict__ lse, int Hq, int Hkv, int super_tiles, int wgs_per_super, int max_pages,
+    float scale_log2e) {
   __shared__ __attribute__((aligned(1024))) char smem[kRing * kBufBytes];
 
-  const int b = blockIdx.z;
-  const int kvh = static_cast<int>(blockIdx.y) / n_groups, hg = static_cast<int>(blockIdx.y) % n_groups;
-  // this workgroup's query heads of the kv head: g heads spread evenly over n_groups workgroups
+  const int b = blockIdx.z, kvh = blockIdx.y;
   const int g = Hq / Hkv;
-  const int nheads = g / n_groups + (hg < g % n_groups ? 1 : 0);
-  const int head0 = hg * (g / n_groups) + min(hg, g % n_groups);
   const int s0 = cu_seqlens[b];
   const int len = cu_seqlens[b + 1] - s0;
   const int n_tiles = (len + kTileQ - 1) / kTileQ;
-  if (static_cast<int>(blockIdx.x) >= n_tiles) return;
-  const int tile = n_tiles - 1 - blockIdx.x;        // late (long) tiles first
+  const int n_super = (n_tiles + super_tiles - 1) / super_tiles;
+  const int sidx = static_cast<int>(blockIdx.x) / wgs_per_super, wg = static_cast<int>(blockIdx.x) % wgs_per_super;
+  if (sidx >= n_super) return;
+  const int tile0 = (n_super - 1 - sidx) * super_tiles;   // late (long) super-tiles first
+  const int units = g * super_tiles;                       // units of a super-tile: u -> (tile0 + u / g, head u % g)
+  if (tile0 + (kHeadsPerWg * wg) / g >= n_tiles) return;   // not even the first unit has a tile
+  // the last step of the workgroup: the tile of its last unit that has one
+  const int last_tile = min(tile0 + min(kHeadsPerWg * wg + kHeadsPerWg - 1, units - 1) / g, n_tiles - 1);
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int n = lane & 15;        // N index of both products: the query within a block
   const int bq = lane >> 4;       // k-group of the MFMA operand layouts
-  const bool computes = wave < nheads;            // (the other waves only move data)
-  const int head = kvh * g + head0 + min(wave, nheads - 1);
+  const int unit = kHeadsPerWg * wg + wave;
+  const int tile = __builtin_amdgcn_readfirstlane(tile0 + unit / g);   // this wave's tile ...
+  const bool computes = unit < units && tile < n_tiles;                // ... if it has one (else the wave only moves data)
+  const int head = kvh * g + unit % g;
   const int q0 = tile * kTileQ;                      // first query token of the tile
   const uint32_t lds0 = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(smem));
 
-  // ---- the tile's own K/V rows go to the sequence's pages (slots past the end of the
-  // sequence are left alone) ----
-  if (hg == 0) {
+  // ---- a tile's own K/V rows go to the sequence's pages, by the workgroup that holds the
+  // tile's unit of head 0 (slots past the end of the sequence are left alone) ----
+  for (int i4 = 0; i4 < kHeadsPerWg; ++i4) {
+    const int u = kHeadsPerWg * wg + i4;
+    const int ut = tile0 + u / g;
+    if (u >= units || u % g != 0 || ut >= n_tiles) continue;
     const int32_t* bt = block_table + static_cast<size_t>(b) * max_pages;
 #pragma unroll
     for (int j = 0; j < 2 * kStepGranules / kThreads; ++j) {
       const int i = tid + j * kThreads;             // i < 512: K, else V; token (i & 511) >> 4, granule i & 15
       const int gi = i & (kStepGranules - 1);
-      const int tok = q0 + (gi >> 4);
+      const int tok = ut * kTileQ + (gi >> 4);
       if (tok < len) {
         const size_t src = (static_cast<size_t>(s0 + tok) * Hkv + kvh) * (kD * 2 / 16) + (gi & 15);
         const size_t dst = (static_cast<size_t>(bt[tok / kP]) * Hkv + kvh) * kPageGranules + (gi & (kPageGranules - 1));
@@ -214,13 +226,15 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2))
   for (int st = 0; st < kAhead; ++st) fetch(st);
   asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(4 * (kAhead - 1)) : "memory");
 
-  // one step.  diag = true: the tile's own tokens (causal mask, end of the sequence)
-  auto do_step = [&](const int step, auto diag) __attribute__((always_inline)) {
+  // one step.  diag = true: the tile's own tokens (causal mask, end of the sequence).
+  // active = false: a step after the wave's own tile (another wave of the workgroup still
+  // needs the rows), or a wave without a unit: it fetches and waits with the others.
+  auto do_step = [&](const int step, const bool active, auto diag) __attribute__((always_inline)) {
     constexpr bool kDiag = decltype(diag)::value;
     const uint32_t boff = static_cast<uint32_t>(step & (kRing - 1)) * kBufBytes;
     fetch(step + kAhead);          // into the buffer of step-1, which every wave left at the last barrier
 
-    if (computes) {
+    if (active) {
       // Scores of the two pages: K rows as the A operand (token = lane & 15), read once for
       // both query blocks.  This lane: query n of each block, tokens 4*bq .. 4*bq+3 of each page.
       // A block whose queries all lie before a page's tokens is fully masked there: its
@@ -354,8 +368,14 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2))
     // the next step has landed, for every wave; all are done with this step's buffer
     asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(4 * (kAhead - 1)) : "memory");
   };
-  for (int step = 0; step < tile; ++step) do_step(step, std::false_type{});
-  do_step(tile, std::true_type{});
+  const int my_last = computes ? tile : -1;
+  int step = 0;
+  for (; step < my_last; ++step) do_step(step, true, std::false_type{});
+  if (computes) {
+    do_step(tile, true, std::true_type{});
+    step = tile + 1;
+  }
+  for (; step <= last_tile; ++step) do_step(step, false, std::false_type{});
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // (the loads past the last step land before the LDS is given back)
 
   // normalise and store: lane (n, bq) owns d = 16*dt + 4*bq + r of query n
@@ -393,15 +413,19 @@ int launch_prefill_attn(const void* q, const void* k, const void* v, const int32
                         float* lse, int B, int Hq, int Hkv, int max_pages, int max_seqlen,
                         float scale, hipStream_t stream) {
   const int g = Hq / Hkv;
-  const int n_groups = (g + kHeadsPerWg - 1) / kHeadsPerWg;
-  const dim3 grid((max_seqlen + kTileQ - 1) / kTileQ, Hkv * n_groups, B);
+  // super-tile of T tiles: the smallest T for which g * T units fill whole workgroups
+  const int gcd4 = (g % 4 == 0) ? 4 : (g % 2 == 0 ? 2 : 1);
+  const int super_tiles = kHeadsPerWg / gcd4;
+  const int wgs_per_super = g * super_tiles / kHeadsPerWg;
+  const int n_tiles_max = (max_seqlen + kTileQ - 1) / kTileQ;
+  const dim3 grid(((n_tiles_max + super_tiles - 1) / super_tiles) * wgs_per_super, Hkv, B);
   const float scale_log2e = scale * kLog2e;
   COPRIS_PRE("prefill_attn_kernel");
   hipLaunchKernelGGL(prefill_attn_kernel, grid, dim3(kThreads), 0, stream,
                      static_cast<const uint16_t*>(q), static_cast<const u32x4*>(k),
                      static_cast<const u32x4*>(v), cu_seqlens, block_table,
                      static_cast<u32x4*>(k_cache), static_cast<u32x4*>(v_cache),
-                     static_cast<uint16_t*>(out), lse, Hq, Hkv, n_groups, max_pages, scale_log2e);
+                     static_cast<uint16_t*>(out), lse, Hq, Hkv, super_tiles, wgs_per_super, max_pages, scale_log2e);
   COPRIS_POST("prefill_attn_kernel");
   return 0;
 }
