@@ -32,6 +32,24 @@ def test_ragged_lengths_every_group_size(R, Hq, Hkv):
     _check_all(R, b, f"{Hq}/{Hkv}")
 
 
+@pytest.mark.parametrize("Hq,Hkv", [(28, 4), (12, 4), (8, 4)])
+def test_empty_sequences_among_others_and_a_loose_length_bound(R, Hq, Hkv):
+    # sequences of length 0 own no tile and no page; max_seqlen may exceed every length (the
+    # grid is then larger than needed and the surplus workgroups leave at once)
+    lens = [0, 33, 0, 0, 130, 1, 0]
+    b = W.make_prefill_case(Hq + 3, lens, Hq, Hkv, 128, W.BF16)
+    d = R.stage_prefill_attn(b, W.BF16)
+    d.max_seqlen = int(d.block_table.shape[1]) * 16          # the loosest bound the call accepts
+    d.run()
+    import torch
+    torch.cuda.synchronize()
+    out = R.out_to_f32(d.out)
+    ref_out, ref_lse, ref_kc, ref_vc = P.oracle_prefill(b, W.BF16)
+    P.check_attn(out, d.lse.cpu().numpy(), ref_out, ref_lse, W.BF16, f"{Hq}/{Hkv} with empties")
+    np.testing.assert_array_equal(R.out_to_f32(d.k_cache), ref_kc)
+    np.testing.assert_array_equal(R.out_to_f32(d.v_cache), ref_vc)
+
+
 @pytest.mark.parametrize("gain", [6.0, 20.0])
 def test_large_scores_move_the_softmax_reference_often(R, gain):
     # queries scaled up: scores spread over tens of log2 units, so the kernel's softmax
