@@ -21,6 +21,12 @@ Who does what:
     device tables here and looked up by row; a trajectory ends at a given length, which is
     what lets the manager plan a stage without waiting for tokens.
 
+With `graph=True` the steps of a stage in which no request enters - all but a few - are one
+HIP graph, captured once per stage and replayed: the manager's commands of such a step fit a
+fixed-size buffer (at most one slot command and one new page per slot; unused entries name
+slot -1, which `copris_rollout_apply` skips), so the host's work per step is `next_step`, one
+small copy and the replay.
+
 Sized for small cases (the stand-in tables of every trajectory are resident).
 """
 from __future__ import annotations
@@ -55,13 +61,16 @@ class _DeviceTables:
 class RolloutLoop:
     def __init__(self, policy: StandInPolicy, pool: int, batch_inputs: int, *, sample_seed: int = 7,
                  temperature: float = 1.0, eps_low: float = 0.2, eps_high: float = 0.28,
-                 page_size: int = 16, page_seed: int = 11, record: bool = True):
+                 page_size: int = 16, page_seed: int = 11, record: bool = True, graph: bool = False):
         self.m = policy
         self.pool, self.batch_inputs = int(pool), int(batch_inputs)
         self.sample_seed, self.temperature = int(sample_seed), float(temperature)
         self.eps_low, self.eps_high = float(eps_low), float(eps_high)
         self.page_size = int(page_size)
         self.record = bool(record)
+        self.graph = bool(graph)
+        if self.graph and self.record:
+            raise ValueError("graph=True replays captured steps: per-step outputs cannot be recorded")
         self.dev = dev = require_gpu()
         self.dt = dtype_code(policy.dtype)
         self.N = policy.samples
@@ -97,6 +106,15 @@ class RolloutLoop:
         self.lm_ws = workspace(binding.lmhead_logprob_workspace_bytes(self.pool, policy.H, policy.V), dev)
         self.stages = []
         self.host_syncs = 0                  # times the host waited for the device
+        # graph mode: the fixed-size command buffer of a captured step (pool slot commands of 4
+        # ints, then pool page commands of 3), and a ring of pinned host copies of it
+        self.cmd_words = 7 * self.pool
+        self.cmd_dev = torch.full((self.cmd_words,), -1, dtype=torch.int32, device=dev) if self.graph else None
+        self.cmd_ring = torch.full((256, self.cmd_words), -1, dtype=torch.int32).pin_memory() if self.graph else None
+        self.cmd_ring_np = self.cmd_ring.numpy() if self.graph else None
+        self.cmd_events = [None] * 256
+        self.cmd_next = 0
+        self.graph_steps = 0                 # steps that ran as a graph replay
 
     # ---- one decode step, all on the stream, nothing read back ---------------------------
     def _prefill(self, plan, tab):
@@ -116,6 +134,9 @@ class RolloutLoop:
         binding.rollout_apply(_upload(plan["cmds"], self.dev), plan["n_slot_cmds"], plan["n_page_cmds"],
                               self.seq_id, self.ctx_len, self.step, self.block_table)
         self._prefill(plan, tab)
+        self._forward_and_sample(tab, stage, log)
+
+    def _forward_and_sample(self, tab, stage, log):
         # the stand-in's forward pass for the position being decoded: a row look-up
         row = tab.row0.index_select(0, self.seq_id.clamp(min=0)) + (self.ctx_len - 1).clamp(min=0)
         q, hidden = tab.q.index_select(0, row), tab.hidden.index_select(0, row)
@@ -129,6 +150,47 @@ class RolloutLoop:
             log.append((self.attn_out.float(), self.attn_lse.clone()))
         binding.traj_append(self.token, self.logprob, self.seq_id, self.step, self.ctx_len, stage,
                             self.buf_token, self.buf_logp, self.buf_tag)
+
+    # ---- graph mode: a step without entering requests ----------------------------------------
+    def _fits_graph(self, plan) -> bool:
+        return (plan["entered"].shape[0] == 0 and plan["n_slot_cmds"] <= self.pool
+                and plan["n_page_cmds"] <= self.pool)
+
+    def _stage_commands(self, plan):
+        """The plan's commands, padded to the captured step's fixed layout, in the next pinned
+        ring entry; returns that entry (a pinned host tensor)."""
+        i = self.cmd_next
+        self.cmd_next = (i + 1) % len(self.cmd_events)
+        if self.cmd_events[i] is not None:
+            self.cmd_events[i].synchronize()     # (the copy that last read this entry; long done)
+        row = self.cmd_ring_np[i]
+        row.fill(-1)
+        ns, npg = plan["n_slot_cmds"], plan["n_page_cmds"]
+        cmds = plan["cmds"]
+        row[:4 * ns] = cmds[:4 * ns]
+        row[4 * self.pool:4 * self.pool + 3 * npg] = cmds[4 * ns:4 * ns + 3 * npg]
+        return i
+
+    def _graph_step(self, plan, tab, stage, state):
+        i = self._stage_commands(plan)
+        self.cmd_dev.copy_(self.cmd_ring[i], non_blocking=True)
+        ev = torch.cuda.Event()
+        ev.record()
+        self.cmd_events[i] = ev
+        if state.get("graph") is None:
+            # capture this stage's step: commands -> pool state, forward pass, append, attention,
+            # sampling, buffer append (the stage tag and the policy's tables are fixed for a stage)
+            g = torch.cuda.CUDAGraph()
+            side = torch.cuda.Stream()
+            side.wait_stream(torch.cuda.current_stream())
+            with torch.cuda.graph(g, stream=side):
+                binding.rollout_apply(self.cmd_dev, self.pool, self.pool, self.seq_id, self.ctx_len, self.step,
+                                      self.block_table)
+                self._forward_and_sample(tab, stage, None)
+            torch.cuda.current_stream().wait_stream(side)
+            state["graph"] = g
+        state["graph"].replay()
+        self.graph_steps += 1
 
     # ---- Eq. 8 and Eq. 2-4 on the batch that leaves ------------------------------------------
     def _train_batch(self, st, tab, stage):
@@ -177,13 +239,19 @@ class RolloutLoop:
         for _ in range(max_stages):
             stage = self.manager.begin_stage()
             tab = _DeviceTables(self.m, stage, self.dev)        # one policy version per stage
-            plans, log = [], []
+            plans, log, state = [], [], {}
             while True:
-                code, plan = self.manager.next_step()
+                # (graph mode keeps no per-step record, so the plan may alias the manager's arrays)
+                code, plan = self.manager.next_step(copy=not self.graph)
                 if code != binding.ROLLOUT_STEP:
                     break
-                self._decode_step(plan, tab, stage, log)
-                plans.append(plan)
+                if self.graph and self._fits_graph(plan):
+                    self._graph_step(plan, tab, stage, state)
+                else:
+                    self._decode_step(plan, tab, stage, log)
+                if not self.graph:
+                    plans.append(plan)
+            state.clear()                        # (the stage's graph goes with its tables)
             if code == binding.ROLLOUT_EXHAUSTED:
                 break
             st = self.manager.end_stage()

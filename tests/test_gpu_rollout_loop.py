@@ -192,3 +192,33 @@ def test_a_larger_pool_follows_the_oracle_schedule():
     for tr in range(loop.n_traj):
         assert (buf_tag[tr, :n_tok[tr]] >= 0).all() and (buf_token[tr, :n_tok[tr]] >= 0).all()
         assert np.isfinite(buf_logp[tr, :n_tok[tr]]).all() and (buf_logp[tr, :n_tok[tr]] <= 0).all()
+
+
+def test_replayed_steps_give_what_eager_steps_give():
+    # the same stages with the steps of a stage captured once and replayed (every step in which
+    # no request enters): buffer, statistics and training batches bit for bit as in eager mode
+    from paper_2511_05589_amd import runner
+    from paper_2511_05589_amd.rollout_loop import RolloutLoop
+    runner.require_gpu()
+    rng = np.random.default_rng(5)
+    I, N, pool, B = 20, 4, 32, 5
+    prompt = rng.integers(4, 60, size=I)
+    resp = np.minimum(np.maximum(np.rint(rng.lognormal(3.0, 0.9, size=(I, N))), 1), 120).astype(np.int64)
+    runs = []
+    for graph in (False, True):
+        policy = W.StandInPolicy(13, prompt, resp, dtype=W.BF16, **DIMS)
+        loop = RolloutLoop(policy, pool, B, sample_seed=5, record=False, graph=graph)
+        stages = loop.run(max_stages=3)
+        runs.append((loop, stages, loop.buffers()))
+    (eager, st_e, buf_e), (replayed, st_g, buf_g) = runs
+    assert replayed.graph_steps > 0 and eager.graph_steps == 0
+    assert replayed.graph_steps < sum(s["stats"]["steps"] for s in st_g)      # steps with entering requests ran eagerly
+    assert len(st_e) == len(st_g) == 3
+    for a, b in zip(buf_e, buf_g):
+        np.testing.assert_array_equal(a, b)
+    for se, sg in zip(st_e, st_g):
+        assert se["stats"] == sg["stats"]
+        for key in ("tokens", "logp_buf", "logp_roll", "split", "logp_cur", "ratio", "ratio_clipped", "seq_sum",
+                    "surr", "grad", "seq_surr"):
+            np.testing.assert_array_equal(se["train"][key], sg["train"][key])
+    assert replayed.host_syncs == 3 and replayed.manager.free_pages() == replayed.num_pages
