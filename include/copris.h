@@ -469,7 +469,12 @@ int copris_rollout_end_stage(copris_rollout* h, copris_stage_stats* stats, int32
  *
  * copris_rollout_apply   applies one plan's commands (copris_rollout_plan.cmds, copied
  *     to the device by the caller): sets seq_id / ctx_len / step of the slots whose
- *     occupant changed and the block-table entries of newly taken pages.
+ *     occupant changed and the block-table entries of newly taken pages.  Layout:
+ *     n_slot_cmds x {slot, trajectory, ctx_len, step}, then n_page_cmds x {slot, page
+ *     index, physical page}.  A command whose slot lies outside [0, pool) (or whose
+ *     page index lies outside [0, max_pages)) is skipped, so a caller may pad a
+ *     buffer of fixed size with slot -1 and pass fixed counts (a step captured in a
+ *     HIP graph).
  * copris_kv_append       k_new, v_new [C, Hkv, D] dtype: the new position's key / value
  *     of every slot goes to token position ctx_len[c] - 1 of its pages
  *     (k_cache[block_table[c][t / P]][kvh][t % P][:]); slots with ctx_len <= 0 are
