@@ -37,6 +37,33 @@ def test_pool_commands(gpu):
         np.testing.assert_array_equal(got.cpu().numpy(), ref)
 
 
+def test_commands_that_name_no_slot_are_skipped(gpu):
+    # a fixed-size command buffer padded with slot -1 (and entries outside the pool or the block
+    # table's row) changes what its valid commands say and nothing else
+    torch, binding, runner, dev = gpu
+    rng = np.random.default_rng(3)
+    pool, max_pages = 64, 5
+    seq_id, ctx, step = rng.integers(-1, 50, pool), rng.integers(0, 99, pool).astype(np.int32), rng.integers(0, 9, pool).astype(np.int32)
+    table = rng.integers(0, 1000, (pool, max_pages)).astype(np.int32)
+    slot_cmds = np.full((pool, 4), -1, dtype=np.int64)
+    valid_s = rng.permutation(pool)[:20]
+    slot_cmds[:20] = np.stack([valid_s, rng.integers(-1, 1 << 20, 20), rng.integers(0, 5000, 20), rng.integers(0, 4000, 20)], 1)
+    slot_cmds[20] = [pool, 7, 7, 7]                      # past the pool
+    page_cmds = np.full((pool, 3), -1, dtype=np.int64)
+    cells = rng.permutation(pool * max_pages)[:30]
+    page_cmds[:30] = np.stack([cells // max_pages, cells % max_pages, rng.integers(0, 1 << 20, 30)], 1)
+    page_cmds[30] = [3, max_pages, 9]                    # past the row
+    page_cmds[31] = [pool + 2, 0, 9]
+    cmds = np.concatenate([slot_cmds.reshape(-1), page_cmds.reshape(-1)]).astype(np.int32)
+    d = [runner.to_device(x, device=dev) for x in (seq_id.astype(np.int64), ctx, step, table)]
+    binding.rollout_apply(runner.to_device(cmds, device=dev), pool, pool, *d)
+    torch.cuda.synchronize()
+    only_valid = np.concatenate([slot_cmds[:20].reshape(-1), page_cmds[:30].reshape(-1)]).astype(np.int32)
+    O.pool_commands_apply(only_valid, 20, 30, seq_id, ctx, step, table)
+    for got, ref in zip(d, (seq_id, ctx, step, table)):
+        np.testing.assert_array_equal(got.cpu().numpy(), ref)
+
+
 @pytest.mark.parametrize("dtype,D,Hkv", [(W.BF16, 128, 4), (W.F32, 64, 2), (W.BF16, 64, 1)])
 def test_kv_append(gpu, dtype, D, Hkv):
     torch, binding, runner, dev = gpu
