@@ -102,14 +102,30 @@ def time_rotating(runs, stream, n, warmup):
 
 
 class ClockSampler:
-    """Samples the GPU core clock the driver reports (the starred level of pp_dpm_sclk) from a
-    host thread while a kernel loop runs."""
+    """Samples the GPU core clock the driver reports (the starred level of pp_dpm_sclk) and the
+    board power (hwmon power1_input) from a host thread while a kernel loop runs."""
 
     def __init__(self):
         paths = sorted(glob.glob("/sys/class/drm/card*/device/pp_dpm_sclk"))
         self.path = paths[0] if paths else None
+        hw = sorted(glob.glob("/sys/class/drm/card*/device/hwmon/hwmon*/power1_input"))
+        self.power_path = hw[0] if hw else None
         self.samples = []
+        self.power = []
+        self.last_power_w = None
         self._stop = threading.Event()
+
+    def power_cap_w(self):
+        try:
+            return round(float(open(self.power_path.replace("power1_input", "power1_cap")).read()) * 1e-6, 1)
+        except Exception:
+            return None
+
+    def _read_power(self):
+        try:
+            return float(open(self.power_path).read()) * 1e-6
+        except Exception:
+            return None
 
     def _read(self):
         try:
@@ -125,6 +141,9 @@ class ClockSampler:
             v = self._read()
             if v is not None:
                 self.samples.append(v)
+            w = self._read_power() if self.power_path else None
+            if w is not None:
+                self.power.append(w)
             time.sleep(0.005)
 
     def measure(self, fn, seconds):
@@ -135,6 +154,7 @@ class ClockSampler:
         if self.path is None:
             return None, None
         self.samples = []
+        self.power = []
         self._stop.clear()
         for _ in range(20):
             fn()
@@ -152,6 +172,8 @@ class ClockSampler:
         self._stop.set()
         th.join()
         body = self.samples[len(self.samples) // 4:]        # the ramp-up is not the sustained state
+        pw = self.power[len(self.power) // 4:]
+        self.last_power_w = round(float(np.median(pw)), 1) if pw else None
         return (round(float(np.median(body)), 1) if body else None), round(dt * 1e3 / calls, 4)
 
 
@@ -343,7 +365,11 @@ def main():
         "call_ms": call,
         "attn_plus_lm": {"algorithmic_GB": round((ab["attn"] + ab["lm"]) / 1e9, 4), "median_ms": round(pair_ms, 4),
                          "achieved_GBps": round(pair_gbs, 1), "frac_hbm": round(pair_gbs / HBM_PEAK_GBS, 4),
-                         "decode_tokens_per_s_attn_lm_only": round(cfg.C / (pair_ms * 1e-3), 1)},
+                         "decode_tokens_per_s_attn_lm_only": round(cfg.C / (pair_ms * 1e-3), 1),
+                         "projection_28_layers": {
+                             "tokens_per_s": round(cfg.C / ((28 * call_ms["attn"] + call_ms["lm"]) * 1e-3), 1),
+                             "note": "context only: C / (28 x attention call + LM-head call), 28 = the layer count of "
+                                     "a 7B decoder of this shape; the other work of a layer is not part of the path"}},
         "kernels": kernels,
         "all_kernel_ms": {k: round(v, 4) for k, v in kernel_ms.items()},
         "input_generation_s": round(t_gen, 1),
@@ -355,15 +381,22 @@ def main():
     if cfg.dtype == W.BF16 and not args.no_extras:
         sampler = ClockSampler()
         mhz_n, ms_n = sampler.measure(lambda: lm.run(stream), 1.0)
+        pw_n = sampler.last_power_w
         zero = clone_device(lm)
         zero.hidden.zero_()
         zero.weight.zero_()
         mhz_z, ms_z = sampler.measure(lambda: zero.run(stream), 1.0)
+        pw_z = sampler.last_power_w
         del zero
         limits["lmhead_core_clock"] = {
-            "seeded_operands": {"sclk_MHz": mhz_n, "ms_per_call": ms_n},
-            "zero_operands": {"sclk_MHz": mhz_z, "ms_per_call": ms_z},
-            "how": "median of the driver's current sclk level sampled every 5 ms over 1 s of back-to-back calls"}
+            "seeded_operands": {"sclk_MHz": mhz_n, "ms_per_call": ms_n, "board_power_W": pw_n},
+            "zero_operands": {"sclk_MHz": mhz_z, "ms_per_call": ms_z, "board_power_W": pw_z},
+            "how": "medians of the driver's current sclk level and of hwmon power1_input, sampled every 5 ms over "
+                   "1 s of back-to-back calls"}
+        mhz_a, ms_a = sampler.measure(lambda: attn.run(stream), 1.0)
+        limits["decode_attn_core_clock"] = {"sclk_MHz": mhz_a, "ms_per_call": ms_a,
+                                            "board_power_W": sampler.last_power_w}
+        limits["board_power_cap_W"] = sampler.power_cap_w()
     result["limits"] = limits
     extras = result["extras"] = {}
 
