@@ -483,6 +483,9 @@ def main():
             "mfma_frac": round(flops / (tl_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
             "traffic": traffic.get("lmhead_gemm_given_kernel"),
             "workload": f"{M} positions x LM head {cfg.H}x{cfg.V} bf16, given tokens"}
+        cs = ClockSampler()
+        mhz, _ms = cs.measure(lambda: td.run(stream), 1.0)
+        extras["token_logprob"].update({"sclk_MHz": mhz, "board_power_W": cs.last_power_w})
         del td
     # ---- re-prefill attention of resumed partial trajectories (one layer): a handful of
     # buffered trajectories with the config's length recipe ----
@@ -502,6 +505,9 @@ def main():
             "traffic": traffic.get("prefill_attn_kernel"),
             "workload": f"{len(plens)} resumed trajectories, lengths {int(plens.min())}..{int(plens.max())}, "
                         f"{cfg.Hq}q/{cfg.Hkv}kv heads, causal, one layer"}
+        cs = ClockSampler()
+        mhz, _ms = cs.measure(lambda: pd.run(stream), 1.0)
+        extras["prefill_attn"].update({"sclk_MHz": mhz, "board_power_W": cs.last_power_w})
         del pd, pb
     # ---- decode attention on the long-tail stress configuration (resumed 32k-token
     # trajectories among short ones: what the split along the context is for) ----
