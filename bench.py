@@ -38,6 +38,7 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16, published
 CACHE_ROTATION_SETS = 8         # distinct input sets for cache-sized workloads
+SETTLE_STEPS = 50      # untimed steps before the timed region (warm-up steps count towards them)
 
 
 def parse_args():
@@ -259,6 +260,11 @@ def main():
         lm.run(stream)
         isd[k % len(isd)].run(stream)
 
+    # The chip needs some tens of launches after staging to reach its sustained state (clocks
+    # ramp up from idle; the LM-head kernel gets ~3 % faster over its first ~50 launches), so the
+    # device is brought there first whatever W is; then the W warm-up steps of the contract.
+    for k in range(max(0, SETTLE_STEPS - args.warmup)):
+        step(k)
     for k in range(args.warmup):
         step(k)
     torch.cuda.synchronize()
@@ -300,12 +306,18 @@ def main():
     # ---- per-kernel durations: the library's launch hook records an event before and
     # after every kernel launch (same stream, same K steps, instrumented pass) ----
     recs = []
+    # (events made beforehand: the hook must cost the host less than the kernels cost the GPU,
+    # or the launches arrive late and every kernel starts on an idle chip)
+    pool = [torch.cuda.Event(enable_timing=True) for _ in range(16 * args.steps + 64)]
+    names = {}
 
     def hook(kernel, phase, _stream, _user):
-        e = torch.cuda.Event(enable_timing=True)
+        e = pool[len(recs)]
         e.record(stream)
-        recs.append((kernel.decode(), phase, e))
+        recs.append((names.setdefault(kernel, kernel.decode()), phase, e))
 
+    for k in range(SETTLE_STEPS):          # (the chip idled while the host worked out the figures above)
+        step(k)
     binding.set_launch_hook(hook)
     for k in range(args.steps):
         step(k)
@@ -354,6 +366,7 @@ def main():
         "metric": "decode tokens/s at fixed concurrency C; achieved HBM GB/s vs MI355X peak",
         "value": round(cfg.C / (ms_per_step * 1e-3), 1), "unit": "tokens/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "settle_steps": max(0, SETTLE_STEPS - args.warmup),
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "bf16" if cfg.dtype == W.BF16 else "f32", "data": "synthetic",
         "config": {"workload": f"config {cfg.index} ({cfg.name}): C={cfg.C}, {cfg.Hq}q/{cfg.Hkv}kv heads, "
