@@ -50,6 +50,22 @@ def test_empty_sequences_among_others_and_a_loose_length_bound(R, Hq, Hkv):
     np.testing.assert_array_equal(R.out_to_f32(d.v_cache), ref_vc)
 
 
+def test_seeded_random_group_sizes_and_lengths(R):
+    # every supported group size against lengths around the page, block, tile and super-tile
+    # boundaries, a few sequences per case (the workgroup <-> (head, tile) mapping differs with
+    # the group size)
+    rng = np.random.default_rng(2024)
+    combos = [(28, 4), (12, 2), (4, 4), (8, 4), (16, 4), (8, 1), (6, 2), (5, 1), (3, 1), (7, 1), (14, 2), (2, 2),
+              (1, 1), (32, 4), (24, 8)]
+    pick = [0, 1, 2, 15, 16, 17, 31, 32, 33, 63, 64, 65, 95, 96, 97, 127, 128, 129, 200, 255, 256, 257, 300, 511]
+    for it, (Hq, Hkv) in enumerate(combos):
+        lens = [int(x) for x in rng.choice(pick, size=int(rng.integers(1, 7)))]
+        if sum(lens) == 0:
+            lens[0] = 5
+        b = W.make_prefill_case(1000 + it, lens, Hq, Hkv, 128, W.BF16)
+        _check_all(R, b, f"{Hq}/{Hkv} lens {lens}")
+
+
 @pytest.mark.parametrize("gain", [6.0, 20.0])
 def test_large_scores_move_the_softmax_reference_often(R, gain):
     # queries scaled up: scores spread over tens of log2 units, so the kernel's softmax
